@@ -1,0 +1,193 @@
+"""Float64 CPU oracle for the KVCompose prefill-time compression pass.
+
+TEST INFRASTRUCTURE ONLY.  This module exists so that the HIP library can be
+checked against the method as the paper defines it.  Only the test-suite, the
+smoke check and the benchmark's CPU-baseline leg may import it; the product
+path never does, and it shares no code with the HIP path.
+
+Every function is the paper's definition written out step by step in float64,
+with no blocking, fusion or reordering, so it can be checked against the paper
+by eye.  Indices are 0-based throughout.
+
+Notation (Preliminary and Section 3 of the paper): Lyr layers, Hq query heads,
+Hkv KV heads, G = Hq/Hkv, head dimension d, N context tokens, M task
+(observation-window) tokens, B = B_total retained composite tokens.
+
+Readings taken where the paper is silent or ambiguous (each is also a library
+convention, stated in the C header):
+
+* The M task queries are an input; every query row attends to all N cached
+  keys with no mask, and the softmax is normalised over exactly those N keys
+  (eq. 3 of the Preliminary: softmax(q K^T / sqrt(d_h)) over the cached keys).
+* The GQA reshape Hq -> (Hkv, G) is row-major: query head q = h*G + g
+  (Section 3.2.2; the printed group equation lost its h index).
+* argsort ties: equal scores keep ascending original index (stable).
+* "top-B_total of P" with ties at the threshold: all entries above the
+  threshold, then entries equal to it in ascending flat index l*N + k.
+* A layer may end with N_l = 0.  No token is force-kept.
+* Rows of K', V' are in descending-importance (rank) order, as the final
+  selection equations literally index K with idx[:N_l].
+* The budget is an integer; B_total = floor((1-r) * Lyr * N) is evaluated by
+  the caller.
+
+Pins (tests/test_oracle_*.py): library softmax in the single-query special
+case, closed forms (identical keys), shift/permutation invariants, row-sum
+identities, one-hot limit, library stable argsort, brute-force enumeration of
+the global selection and of per-head subsets on tiny inputs, budget identities.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+AGG_MAX = 0
+AGG_MEAN = 1
+
+
+# --------------------------------------------------------------------------
+# input widening (the oracle's own; the HIP path consumes the raw bits)
+# --------------------------------------------------------------------------
+def widen(x: np.ndarray) -> np.ndarray:
+    """Exact float64 value of a float32 array or of bf16 bit patterns (uint16)."""
+    x = np.asarray(x)
+    if x.dtype == np.uint16:
+        return (x.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    return x.astype(np.float64)
+
+
+def _agg(x: np.ndarray, op: int, axis: int) -> np.ndarray:
+    if op == AGG_MAX:
+        return x.max(axis=axis)
+    if op == AGG_MEAN:
+        return x.mean(axis=axis)
+    raise ValueError("unknown aggregation operator")
+
+
+# --------------------------------------------------------------------------
+# Section 3.2.2: attention collection and aggregation
+# --------------------------------------------------------------------------
+def attention(q_rows: np.ndarray, keys: np.ndarray, scale: float) -> np.ndarray:
+    """A[m, c] = softmax_c(q_m . k_c * scale) for M query rows and N cached keys.
+
+    Preliminary eq. 3 applied to each task token; the softmax runs over the N
+    cached keys only.
+    """
+    s = (q_rows @ keys.T) * scale                     # [M, N]
+    s = s - s.max(axis=1, keepdims=True)
+    e = np.exp(s)
+    return e / e.sum(axis=1, keepdims=True)
+
+
+def score_layer(q, k, *, agg_task=AGG_MAX, agg_group=AGG_MEAN, add_head_mean=True,
+                scale=None) -> np.ndarray:
+    """S[h, c] for one layer of one sequence.
+
+    q: [Hq, M, d], k: [Hkv, N, d] (float64).  Follows, in order, the three
+    equations of Section 3.2.2: aggregation over task tokens (eq. 14),
+    aggregation over the query heads of a KV group (eq. 15) and the head-mean
+    augmentation that follows them.
+    """
+    hq, m, d = q.shape
+    hkv, n, _ = k.shape
+    g = hq // hkv
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    s_task = np.empty((hq, n))
+    for qh in range(hq):
+        a = attention(q[qh], k[qh // g], scale)       # [M, N]: A^(l, qh, c, m)
+        s_task[qh] = _agg(a, agg_task, axis=0)        # eq. 14
+    s_group = _agg(s_task.reshape(hkv, g, n), agg_group, axis=1)   # eq. 15
+    if add_head_mean:
+        return s_group + s_group.sum(axis=0, keepdims=True) / hkv  # augmentation
+    return s_group
+
+
+# --------------------------------------------------------------------------
+# Section 3.3: composite tokens
+# --------------------------------------------------------------------------
+def head_rank(s: np.ndarray):
+    """idx[..., k] = position with the k-th largest score (ties: lower index
+    first) and S'[..., k] = S[..., idx[..., k]]  (Section 3.3: the per-head
+    descending argsort, eq. 17, and the rank-aligned scores defined after it).
+
+    Written as a plain loop-free definition: sort pairs (-score, index)
+    lexicographically.
+    """
+    s = np.asarray(s)
+    n = s.shape[-1]
+    flat = s.reshape(-1, n)
+    idx = np.empty(flat.shape, dtype=np.int64)
+    pos = np.arange(n)
+    for r in range(flat.shape[0]):
+        idx[r] = np.lexsort((pos, -flat[r]))          # primary key -score, then index
+    s_sorted = np.take_along_axis(flat, idx, axis=1)
+    return idx.reshape(s.shape), s_sorted.reshape(s.shape)
+
+
+def composite(s_sorted: np.ndarray, agg_head=AGG_MEAN) -> np.ndarray:
+    """I[k] = Agg_h S'[h, k] for one layer: the composite importance score that
+    Section 3.3 defines right after the rank-aligned scores.  s_sorted: [Hkv, N]."""
+    return _agg(np.asarray(s_sorted, dtype=np.float64), agg_head, axis=0)
+
+
+def global_select(i_all: np.ndarray, budget: int):
+    """Per-layer lengths from the global pool (Section 3.3, pool / budget /
+    N_l equations).
+
+    i_all: [Lyr, N].  The pool P holds all Lyr*N composite scores; the top
+    ``budget`` of them are taken (ties by ascending flat index l*N + k) and
+    N_l counts how many of the taken entries lie in layer l.  Returns
+    (lengths int64 [Lyr], tau) with tau the smallest taken score (None when
+    budget == 0).
+    """
+    i_all = np.asarray(i_all)
+    lyr, n = i_all.shape
+    if not 0 <= budget <= lyr * n:
+        raise ValueError("budget out of range")
+    pool = i_all.reshape(-1)
+    order = np.lexsort((np.arange(pool.size), -pool))
+    taken = order[:budget]
+    lengths = np.bincount(taken // n, minlength=lyr).astype(np.int64)
+    tau = pool[taken[-1]] if budget > 0 else None
+    return lengths, tau
+
+
+def gather(x: np.ndarray, idx: np.ndarray, n_keep: int) -> np.ndarray:
+    """X'[h, k, :] = X[h, idx[h, k], :], k < n_keep (final selection equations)."""
+    hkv = x.shape[0]
+    out = np.empty((hkv, n_keep) + x.shape[2:], dtype=x.dtype)
+    for h in range(hkv):
+        out[h] = x[h, idx[h, :n_keep]]
+    return out
+
+
+# --------------------------------------------------------------------------
+# whole pass for one sequence
+# --------------------------------------------------------------------------
+def compress(q_layers, k_layers, v_layers, budget: int, *, agg_task=AGG_MAX,
+             agg_group=AGG_MEAN, agg_head=AGG_MEAN, add_head_mean=True, scale=None):
+    """Run the pass on one sequence.
+
+    q_layers[l]: [Hq, M, d]; k_layers[l], v_layers[l]: [Hkv, N, d]; any of
+    float32 / float64 / bf16 bits (uint16).  K' and V' keep the input dtype
+    (bit copies).  Returns a dict with every intermediate.
+    """
+    lyr = len(k_layers)
+    s_all, idx_all, ssorted_all, i_all = [], [], [], []
+    for l in range(lyr):
+        s = score_layer(widen(q_layers[l]), widen(k_layers[l]), agg_task=agg_task,
+                        agg_group=agg_group, add_head_mean=add_head_mean, scale=scale)
+        idx, s_sorted = head_rank(s)
+        s_all.append(s)
+        idx_all.append(idx)
+        ssorted_all.append(s_sorted)
+        i_all.append(composite(s_sorted, agg_head))
+    i_all = np.stack(i_all)
+    lengths, tau = global_select(i_all, budget)
+    k_out = [gather(np.asarray(k_layers[l]), idx_all[l], int(lengths[l])) for l in range(lyr)]
+    v_out = None
+    if v_layers is not None:
+        v_out = [gather(np.asarray(v_layers[l]), idx_all[l], int(lengths[l])) for l in range(lyr)]
+    return {
+        "S": np.stack(s_all), "idx": np.stack(idx_all), "S_sorted": np.stack(ssorted_all),
+        "I": i_all, "tau": tau, "lengths": lengths, "K_out": k_out, "V_out": v_out,
+    }
