@@ -1,0 +1,198 @@
+/*
+ * kvc.h - C ABI of the KVCompose prefill-time KV-cache compression pass for
+ * AMD MI355X (gfx950).
+ *
+ * The pass (paper Sections 3.2.2 and 3.3), per sequence:
+ *   1. kvc_score          S[l,h,c]  attention of the M observation-window (task)
+ *                         queries over all N cached keys, aggregated over task
+ *                         tokens, over the query heads of a KV group, plus the
+ *                         mean over KV heads            (Section 3.2.2)
+ *   2. kvc_head_rank      idx[l,h,:] stable descending argsort of S[l,h,:] and
+ *                         the rank-aligned scores S'     (Section 3.3, eq. 17)
+ *   3. kvc_composite      I[l,k] = Agg_h S'[l,h,k]       (Section 3.3)
+ *   4. kvc_global_select  top-B_total of the pool of all I[l,k]; N_l = how many
+ *                         of them lie in layer l         (Section 3.3)
+ *   5. kvc_gather         K'[l][h,k,:] = K[l][h, idx[l,h,k], :], k < N_l, same
+ *                         for V                          (Section 3.3, last eqs.)
+ *   kvc_compress runs 1-5 back to back on one stream.
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ * Notation: Bt sequences, Lyr layers, Hq query heads, Hkv KV heads, G = Hq/Hkv,
+ * d head dimension, M window (task) tokens, N_b tokens of sequence b,
+ * T = sum_b N_b.  All indices are 0-based.
+ *
+ * Memory: every pointer marked "device" is memory of the current HIP device,
+ * owned by the caller; pointers marked "host" are ordinary host memory read
+ * before the call returns.  The library allocates no device memory, keeps no
+ * pointer after return and never synchronises the stream: all work is
+ * enqueued on `stream` (a hipStream_t passed as void*, NULL = default stream).
+ * Results are valid once the stream has been synchronised by the caller.
+ *
+ * Layouts (row-major, innermost last):
+ *   q[l]   device, [Bt, Hq, M, d]       task queries of layer l (already
+ *                                       position-encoded; used as given)
+ *   k[l]   device, [Hkv, T, d]          keys of layer l; sequence b owns tokens
+ *   v[l]   device, [Hkv, T, d]          [cu_seqlens[b], cu_seqlens[b+1])
+ *   q, k, v themselves are host arrays of Lyr device pointers.
+ *   cu_seqlens  host, int64 [Bt+1], cu_seqlens[0] = 0, non-decreasing.
+ *   S, S_sorted device, float [Lyr, Hkv, T]
+ *   idx         device, int32 [Lyr, Hkv, T]; values are token positions inside
+ *               their own sequence (0 .. N_b-1)
+ *   I           device, float [Lyr, T]
+ *   lengths     device, int32 [Bt*Lyr], lengths[b*Lyr+l] = N_{b,l}
+ *   offsets     device, int64 [Bt*Lyr+1], exclusive prefix sum of lengths in
+ *               that order; offsets[Bt*Lyr] = sum_b budget[b]
+ *   k_out,v_out device pools of (sum_b budget[b]) * Hkv * d elements of the
+ *               input dtype.  Block (b,l) is the dense tensor [Hkv, N_{b,l}, d]
+ *               (the uniform per-layer layout of the problem statement,
+ *               constraint C2) starting at element offsets[b*Lyr+l]*Hkv*d.
+ *               Rows are in descending-importance (rank) order.
+ *
+ * Readings of the paper fixed by this library: no attention mask (each task
+ * query sees all N_b cached keys of its sequence, softmax over exactly those);
+ * query head q belongs to KV head q / G; equal scores rank by ascending token
+ * index; ties at the global threshold are taken by ascending (layer, rank);
+ * a layer may keep 0 tokens; nothing is force-kept; sequences of a batch are
+ * independent, each with its own budget.  Non-finite inputs are undefined.
+ *
+ * Errors: every function returns a kvc_status.  All argument checks run on the
+ * host before the first HIP call; on any error nothing has been enqueued,
+ * except KVC_ERR_HIP which reports a failed launch (kvc_last_error() has the
+ * HIP message).  No function aborts or throws.
+ *
+ * Limits: Bt <= KVC_MAX_BATCH, Lyr <= KVC_MAX_LAYERS, T < 2^31,
+ * d * sizeof(element) a multiple of 16 bytes and d <= 256.
+ */
+#ifndef KVC_H
+#define KVC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define KVC_MAX_BATCH 64
+#define KVC_MAX_LAYERS 128
+
+typedef enum {
+  KVC_OK = 0,
+  KVC_ERR_INVALID_ARG = 1, /* null pointer, inconsistent sizes, out-of-range value */
+  KVC_ERR_UNSUPPORTED = 2, /* well-formed but outside the supported shapes */
+  KVC_ERR_WORKSPACE = 3,   /* workspace missing, misaligned or too small */
+  KVC_ERR_HIP = 4          /* a HIP runtime call failed */
+} kvc_status;
+
+typedef enum { KVC_F32 = 0, KVC_BF16 = 1 } kvc_dtype;
+typedef enum { KVC_AGG_MAX = 0, KVC_AGG_MEAN = 1 } kvc_agg;
+
+/* Problem description.  Defaults of the paper's experiments (Section 4.2):
+ * agg_task = MAX, agg_group = MEAN, agg_head = MEAN, add_head_mean = 1. */
+typedef struct kvc_params {
+  int32_t batch;         /* Bt  */
+  int32_t layers;        /* Lyr */
+  int32_t hq;            /* Hq  */
+  int32_t hkv;           /* Hkv, divides Hq */
+  int32_t head_dim;      /* d   */
+  int32_t window;        /* M   */
+  int32_t dtype;         /* kvc_dtype of q, k, v, k_out, v_out */
+  int32_t agg_task;      /* kvc_agg over the M task tokens        (eq. 14) */
+  int32_t agg_group;     /* kvc_agg over the G heads of a KV group (eq. 15) */
+  int32_t agg_head;      /* kvc_agg over KV heads for I            (Section 3.3) */
+  int32_t add_head_mean; /* 1: add the mean over KV heads to S (Section 3.2.2) */
+  float softmax_scale;   /* 0 => 1/sqrt(d) (Preliminary eq. 3) */
+} kvc_params;
+
+typedef struct kvc_inputs {
+  const void* const* q;      /* host array [Lyr] of device pointers */
+  const void* const* k;      /* host array [Lyr] of device pointers */
+  const void* const* v;      /* host array [Lyr] of device pointers */
+  const int64_t* cu_seqlens; /* host, [Bt+1] */
+  const int64_t* budget;     /* host, [Bt]: B_total of each sequence,
+                                0 <= budget[b] <= Lyr * N_b */
+} kvc_inputs;
+
+typedef struct kvc_outputs {
+  void* k_out;      /* device pool, see layouts */
+  void* v_out;      /* device pool */
+  int32_t* lengths; /* device [Bt*Lyr] */
+  int64_t* offsets; /* device [Bt*Lyr+1] */
+  /* Optional taps on the intermediates; each may be NULL (then it lives in the
+   * workspace).  Shapes as in "Layouts". */
+  float* scores;   /* S */
+  int32_t* idx;    /* idx */
+  float* s_sorted; /* S' */
+  float* composite;/* I */
+  float* tau;      /* device [Bt]: smallest retained composite score
+                      (+inf when budget[b] == 0) */
+} kvc_outputs;
+
+int kvc_version(void);
+const char* kvc_status_string(int status);
+/* Message of the last KVC_ERR_* raised on the calling thread ("" if none). */
+const char* kvc_last_error(void);
+
+/* floor(keep_percent/100 * layers * n) in integer arithmetic: the paper's
+ * B_total = floor((1 - r_target) * L * N) with 1 - r_target = keep_percent/100
+ * (Section 3.3).  Returns -1 on invalid arguments. */
+int64_t kvc_budget(int32_t keep_percent, int32_t layers, int64_t n);
+
+/* Bytes of device workspace that suffice for kvc_compress and for every stage
+ * entry point on this problem.  max_seqlen = max_b N_b.  The workspace must be
+ * 256-byte aligned; its contents on entry are irrelevant and on exit
+ * unspecified. */
+kvc_status kvc_workspace_size(const kvc_params* params, int64_t total_tokens,
+                              int64_t max_seqlen, size_t* bytes);
+
+/* Stage 1, Section 3.2.2.  For every sequence b, layer l, KV head h, token c:
+ *   A[q,m,c]  = softmax_c( Q[l,b,q,m,:] . K[l,h,c,:] * scale )   (all N_b keys)
+ *   S_task    = Agg_task over m;  S_group = Agg_group over q in [hG, hG+G);
+ *   S[l,h,c]  = S_group[h,c] + (add_head_mean ? mean_i S_group[i,c] : 0).
+ * bf16 inputs are multiplied on the matrix cores with fp32 accumulation; all
+ * later arithmetic is fp32.  Writes S (device, float [Lyr,Hkv,T]). */
+kvc_status kvc_score(const kvc_params* params, const void* const* q,
+                     const void* const* k, const int64_t* cu_seqlens, float* S,
+                     void* workspace, size_t workspace_bytes, void* stream);
+
+/* Stage 2, Section 3.3 eq. 17 and the rank-aligned scores after it.  For each
+ * (l,h) and sequence: idx = positions sorted by S descending, equal scores in
+ * ascending position; S_sorted[k] = S[idx[k]].  -0 and +0 compare equal. */
+kvc_status kvc_head_rank(const kvc_params* params, const float* S,
+                         const int64_t* cu_seqlens, int32_t* idx, float* S_sorted,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/* Stage 3, Section 3.3 composite importance: I[l,k] = Agg_head over h of
+ * S_sorted[l,h,k]; the mean is summed in ascending h in fp32. */
+kvc_status kvc_composite(const kvc_params* params, const float* S_sorted,
+                         const int64_t* cu_seqlens, float* I, void* stream);
+
+/* Stage 4, Section 3.3 pool / budget / N_l.  Per sequence: tau = budget-th
+ * largest of the Lyr*N_b values I[l, seq tokens]; lengths = count of I > tau
+ * plus, in ascending layer order, as many I == tau as still fit the budget.
+ * offsets = exclusive prefix sum of lengths over (b,l).  tau may be NULL. */
+kvc_status kvc_global_select(const kvc_params* params, const float* I,
+                             const int64_t* cu_seqlens, const int64_t* budget,
+                             float* tau, int32_t* lengths, int64_t* offsets,
+                             void* workspace, size_t workspace_bytes, void* stream);
+
+/* Stage 5, Section 3.3 final selection.  Copies rows idx[l,h,0..N_{b,l}) of
+ * K and V (bit copies) into the pools; lengths/offsets are read on the device.
+ * total_budget = sum_b budget[b] (host value, sizes the launch).  v and v_out
+ * may both be NULL to gather keys only. */
+kvc_status kvc_gather(const kvc_params* params, const void* const* k,
+                      const void* const* v, const int32_t* idx,
+                      const int32_t* lengths, const int64_t* offsets,
+                      const int64_t* cu_seqlens, int64_t total_budget, void* k_out,
+                      void* v_out, void* stream);
+
+/* The whole pass: stages 1-5 on one stream, no host synchronisation. */
+kvc_status kvc_compress(const kvc_params* params, const kvc_inputs* in,
+                        const kvc_outputs* out, void* workspace,
+                        size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVC_H */

@@ -1,0 +1,82 @@
+// Internal declarations shared by the host API and the gfx950 kernels.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "kvc.h"
+
+namespace kvc {
+
+// Sequence table passed to kernels by value (no device copy of cu_seqlens).
+struct SeqTable {
+  int32_t batch;
+  int32_t cu[KVC_MAX_BATCH + 1];
+};
+
+// Per-layer device pointers passed by value.
+struct PtrTable {
+  const void* p[KVC_MAX_LAYERS];
+};
+
+struct Problem {
+  int32_t batch, layers, hq, hkv, group, d, window, dtype;
+  int32_t agg_task, agg_group, agg_head, add_head_mean;
+  float scale;        // softmax scale actually used
+  int64_t total;      // T
+  int64_t max_seqlen;
+  SeqTable seq;
+};
+
+inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+inline int esize(int dtype) { return dtype == KVC_BF16 ? 2 : 4; }
+
+// Host-side error plumbing (thread local message).
+void set_error(const char* fmt, ...);
+kvc_status hip_fail(hipError_t e, const char* what);
+
+#define KVC_HIP_LAUNCH_CHECK(what)                        \
+  do {                                                    \
+    hipError_t e__ = hipGetLastError();                   \
+    if (e__ != hipSuccess) return kvc::hip_fail(e__, what); \
+  } while (0)
+
+// ---------------------------------------------------------------------------
+// Stage launchers (each enqueues on `stream`, validates nothing).
+// ---------------------------------------------------------------------------
+size_t score_workspace_bytes(const Problem& pb);
+kvc_status launch_score(const Problem& pb, const void* const* q, const void* const* k,
+                        float* S, void* ws, hipStream_t stream);
+
+size_t rank_workspace_bytes(const Problem& pb);
+kvc_status launch_head_rank(const Problem& pb, const float* S, int32_t* idx, float* S_sorted,
+                            void* ws, hipStream_t stream);
+
+kvc_status launch_composite(const Problem& pb, const float* S_sorted, float* I,
+                            hipStream_t stream);
+
+size_t select_workspace_bytes(const Problem& pb);
+kvc_status launch_global_select(const Problem& pb, const float* I, const int64_t* budget,
+                                float* tau, int32_t* lengths, int64_t* offsets, void* ws,
+                                hipStream_t stream);
+
+kvc_status launch_gather(const Problem& pb, const void* const* k, const void* const* v,
+                         const int32_t* idx, const int32_t* lengths, const int64_t* offsets,
+                         int64_t total_budget, void* k_out, void* v_out, hipStream_t stream);
+
+// ---------------------------------------------------------------------------
+// Device helpers
+// ---------------------------------------------------------------------------
+// Monotone map from float to unsigned: a < b  <=>  key(a) < key(b); -0 maps to
+// the same key as +0.
+__device__ __forceinline__ uint32_t float_to_ordered(float f) {
+  uint32_t u = __float_as_uint(f);
+  if (u == 0x80000000u) u = 0u;
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float ordered_to_float(uint32_t k) {
+  uint32_t u = (k & 0x80000000u) ? (k & 0x7fffffffu) : ~k;
+  return __uint_as_float(u);
+}
+
+}  // namespace kvc

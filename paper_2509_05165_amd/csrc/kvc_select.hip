@@ -1,0 +1,214 @@
+// kvc_global_select: the budget-th largest composite score of each sequence's
+// pool {I[l,k]} and the per-layer lengths N_l it induces (Section 3.3: global
+// pool, B_total, N_l).
+//
+// Radix select on the order-preserving integer image of the fp32 scores, three
+// digits of 11/11/10 bits from the top: each pass histograms the candidates
+// that match the prefix found so far, a one-workgroup step picks the digit
+// that holds the wanted rank.  A last sweep counts, per layer, the entries
+// above the threshold and those equal to it; ties are granted in ascending
+// layer order until the budget is met (within a layer the tied entries are the
+// ranks right after the ones above the threshold, so each layer keeps a prefix).
+#include "kvc_internal.h"
+
+namespace kvc {
+
+namespace {
+
+constexpr int SEL_BINS = 2048;
+constexpr int SEL_THREADS = 256;
+constexpr int SEL_PER_BLOCK = SEL_THREADS * 8;
+
+struct SelState {
+  uint32_t prefix;       // bits of the threshold key fixed so far
+  uint32_t pad;
+  uint64_t remaining;    // rank still to descend inside the prefix bucket (1-based)
+};
+
+struct BudgetTable { int64_t b[KVC_MAX_BATCH]; };
+
+__device__ __forceinline__ void digit_of(int pass, uint32_t key, uint32_t* digit, uint32_t* hi) {
+  // pass 0: bits 31..21, pass 1: bits 20..10, pass 2: bits 9..0
+  if (pass == 0) { *digit = key >> 21; *hi = 0; }
+  else if (pass == 1) { *digit = (key >> 10) & 2047u; *hi = key >> 21; }
+  else { *digit = key & 1023u; *hi = key >> 10; }
+}
+
+__global__ void select_init(uint32_t* hist, int count, SelState* state, BudgetTable budget,
+                            int batch) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < count) hist[i] = 0;
+  if (i < batch) { state[i].prefix = 0; state[i].pad = 0; state[i].remaining = (uint64_t)budget.b[i]; }
+}
+
+// grid: (token blocks, layers, batch)
+__global__ __launch_bounds__(SEL_THREADS) void select_hist(
+    const float* __restrict__ I, SeqTable seq, int total, int pass,
+    const SelState* __restrict__ state, uint32_t* __restrict__ hist /* [batch][3][SEL_BINS] */) {
+  __shared__ uint32_t lh[SEL_BINS];
+  const int b = blockIdx.z;
+  const int tok0 = seq.cu[b], n = seq.cu[b + 1] - tok0;
+  const int begin = blockIdx.x * SEL_PER_BLOCK;
+  if (begin >= n) return;
+  const int end = min(n, begin + SEL_PER_BLOCK);
+  for (int i = threadIdx.x; i < SEL_BINS; i += SEL_THREADS) lh[i] = 0;
+  __syncthreads();
+  const uint32_t want_hi = pass == 0 ? 0u : (pass == 1 ? state[b].prefix >> 21 : state[b].prefix >> 10);
+  const float* row = I + (size_t)blockIdx.y * total + tok0;
+  for (int i = begin + threadIdx.x; i < end; i += SEL_THREADS) {
+    uint32_t digit, hi;
+    digit_of(pass, float_to_ordered(row[i]), &digit, &hi);
+    if (hi == want_hi) atomicAdd(&lh[digit], 1u);
+  }
+  __syncthreads();
+  uint32_t* gh = hist + ((size_t)b * 3 + pass) * SEL_BINS;
+  for (int i = threadIdx.x; i < SEL_BINS; i += SEL_THREADS)
+    if (lh[i]) atomicAdd(&gh[i], lh[i]);
+}
+
+// grid: (batch); picks the digit whose bucket holds the wanted rank, walking
+// from the largest digit down.
+__global__ __launch_bounds__(SEL_THREADS) void select_find(int pass, const uint32_t* __restrict__ hist,
+                                                           SelState* state) {
+  __shared__ uint32_t sums[SEL_THREADS];
+  const int b = blockIdx.x;
+  const uint64_t want = state[b].remaining;
+  if (want == 0) return;                       // budget 0: nothing to find
+  const uint32_t* gh = hist + ((size_t)b * 3 + pass) * SEL_BINS;
+  const int bins = pass == 2 ? 1024 : SEL_BINS;
+  const int per = bins / SEL_THREADS;          // 8 or 4 bins per thread
+  // thread t owns bins [bins - (t+1)*per, bins - t*per): descending order
+  const int t = threadIdx.x;
+  uint32_t mine = 0;
+  for (int j = 0; j < per; ++j) mine += gh[bins - 1 - (t * per + j)];
+  sums[t] = mine;
+  __syncthreads();
+  if (t == 0) {
+    uint64_t run = 0;
+    int owner = SEL_THREADS - 1;
+    for (int i = 0; i < SEL_THREADS; ++i) {
+      if (run + sums[i] >= want) { owner = i; break; }
+      run += sums[i];
+    }
+    uint32_t digit = 0;
+    for (int j = 0; j < per; ++j) {
+      const int bin = bins - 1 - (owner * per + j);
+      const uint32_t c = gh[bin];
+      if (run + c >= want) { digit = (uint32_t)bin; break; }
+      run += c;
+      digit = (uint32_t)bin;
+    }
+    const uint32_t shift = pass == 0 ? 21u : (pass == 1 ? 10u : 0u);
+    state[b].prefix |= digit << shift;
+    state[b].remaining = want - run;           // rank inside the chosen bucket
+  }
+}
+
+// grid: (token blocks, layers, batch): counts[b][l] = {#(I > tau), #(I == tau)}
+__global__ __launch_bounds__(SEL_THREADS) void select_count(
+    const float* __restrict__ I, SeqTable seq, int total, int layers,
+    const SelState* __restrict__ state, uint32_t* __restrict__ counts) {
+  __shared__ uint32_t sh[2];
+  const int b = blockIdx.z;
+  const int tok0 = seq.cu[b], n = seq.cu[b + 1] - tok0;
+  const int begin = blockIdx.x * SEL_PER_BLOCK;
+  if (begin >= n) return;
+  const int end = min(n, begin + SEL_PER_BLOCK);
+  if (threadIdx.x < 2) sh[threadIdx.x] = 0;
+  __syncthreads();
+  const uint32_t tau = state[b].prefix;
+  const float* row = I + (size_t)blockIdx.y * total + tok0;
+  uint32_t gt = 0, eq = 0;
+  for (int i = begin + threadIdx.x; i < end; i += SEL_THREADS) {
+    const uint32_t key = float_to_ordered(row[i]);
+    gt += key > tau;
+    eq += key == tau;
+  }
+  for (int off = 32; off >= 1; off >>= 1) { gt += __shfl_xor(gt, off); eq += __shfl_xor(eq, off); }
+  if ((threadIdx.x & 63) == 0) { atomicAdd(&sh[0], gt); atomicAdd(&sh[1], eq); }
+  __syncthreads();
+  if (threadIdx.x < 2 && sh[threadIdx.x])
+    atomicAdd(&counts[((size_t)b * layers + blockIdx.y) * 2 + threadIdx.x], sh[threadIdx.x]);
+}
+
+// one thread: lengths, offsets, tau
+__global__ void select_finalize(SeqTable seq, int layers, BudgetTable budget,
+                                const SelState* __restrict__ state,
+                                const uint32_t* __restrict__ counts, float* tau,
+                                int32_t* lengths, int64_t* offsets) {
+  if (blockIdx.x != 0 || threadIdx.x != 0) return;
+  int64_t off = 0;
+  for (int b = 0; b < seq.batch; ++b) {
+    const int64_t want = budget.b[b];
+    if (tau) tau[b] = want > 0 ? ordered_to_float(state[b].prefix) : __builtin_inff();
+    int64_t above = 0;
+    for (int l = 0; l < layers; ++l) above += counts[((size_t)b * layers + l) * 2];
+    int64_t ties_left = want - above;
+    for (int l = 0; l < layers; ++l) {
+      int64_t len = 0;
+      if (want > 0) {
+        const int64_t gt = counts[((size_t)b * layers + l) * 2];
+        const int64_t eq = counts[((size_t)b * layers + l) * 2 + 1];
+        const int64_t take = eq < ties_left ? eq : ties_left;
+        ties_left -= take;
+        len = gt + take;
+      }
+      lengths[b * layers + l] = (int32_t)len;
+      offsets[b * layers + l] = off;
+      off += len;
+    }
+  }
+  offsets[seq.batch * layers] = off;
+}
+
+struct SelectLayout { size_t off_hist, off_counts, off_state, total; int words; };
+
+SelectLayout select_layout(const Problem& pb) {
+  SelectLayout L{};
+  size_t cur = 0;
+  const size_t hist_words = size_t(pb.batch) * 3 * SEL_BINS;
+  const size_t count_words = size_t(pb.batch) * pb.layers * 2;
+  L.off_hist = cur;   cur += hist_words * 4;
+  L.off_counts = cur; cur += align_up(count_words * 4);
+  L.words = int((cur) / 4);                   // hist and counts are zeroed together
+  L.off_state = cur;  cur += align_up(size_t(pb.batch) * sizeof(SelState));
+  L.total = cur;
+  return L;
+}
+
+}  // namespace
+
+size_t select_workspace_bytes(const Problem& pb) { return select_layout(pb).total; }
+
+kvc_status launch_global_select(const Problem& pb, const float* I, const int64_t* budget,
+                                float* tau, int32_t* lengths, int64_t* offsets, void* ws,
+                                hipStream_t stream) {
+  const SelectLayout L = select_layout(pb);
+  char* w = static_cast<char*>(ws);
+  uint32_t* hist = reinterpret_cast<uint32_t*>(w + L.off_hist);
+  uint32_t* counts = reinterpret_cast<uint32_t*>(w + L.off_counts);
+  SelState* state = reinterpret_cast<SelState*>(w + L.off_state);
+  BudgetTable bt{};
+  for (int b = 0; b < pb.batch; ++b) bt.b[b] = budget[b];
+  const int total = int(pb.total);
+
+  select_init<<<(L.words + 255) / 256, 256, 0, stream>>>(hist, L.words, state, bt, pb.batch);
+  KVC_HIP_LAUNCH_CHECK("select_init");
+  if (pb.max_seqlen > 0) {
+    dim3 grid((unsigned)((pb.max_seqlen + SEL_PER_BLOCK - 1) / SEL_PER_BLOCK), pb.layers, pb.batch);
+    for (int pass = 0; pass < 3; ++pass) {
+      select_hist<<<grid, SEL_THREADS, 0, stream>>>(I, pb.seq, total, pass, state, hist);
+      KVC_HIP_LAUNCH_CHECK("select_hist");
+      select_find<<<pb.batch, SEL_THREADS, 0, stream>>>(pass, hist, state);
+      KVC_HIP_LAUNCH_CHECK("select_find");
+    }
+    select_count<<<grid, SEL_THREADS, 0, stream>>>(I, pb.seq, total, pb.layers, state, counts);
+    KVC_HIP_LAUNCH_CHECK("select_count");
+  }
+  select_finalize<<<1, 64, 0, stream>>>(pb.seq, pb.layers, bt, state, counts, tau, lengths,
+                                        offsets);
+  KVC_HIP_LAUNCH_CHECK("select_finalize");
+  return KVC_OK;
+}
+
+}  // namespace kvc

@@ -1,0 +1,169 @@
+"""Helpers shared by the GPU parity tests: build a seeded workload, run the
+oracle on it, upload it, call the C ABI through the Python binding."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import paper_2509_05165_amd as kv
+import workloads as wl
+from oracle import kvc_oracle as orc
+
+EPS = 2e-3          # score tolerance of the benchmark spec
+
+
+class Workload:
+    """Host copy of one seeded workload, packed the way the library wants it."""
+
+    def __init__(self, cfg, seed=0, lens=None, budgets=None):
+        self.cfg = cfg
+        self.lens = np.asarray(lens if lens is not None else wl.seq_lens(cfg, seed), dtype=np.int64)
+        self.cu = np.concatenate([[0], np.cumsum(self.lens)]).astype(np.int64)
+        self.total = int(self.cu[-1])
+        self.budgets = [int(x) for x in (budgets if budgets is not None else
+                                         [wl.budget_for(cfg, n) for n in self.lens])]
+        self.q, self.k, self.v = [], [], []        # per layer, packed over the batch
+        self.seq = [[None] * cfg.layers for _ in range(cfg.batch)]   # per (b, l): (q, k, v)
+        for l in range(cfg.layers):
+            qs, ks, vs = [], [], []
+            for b in range(cfg.batch):
+                q, k, v = wl.make_layer(cfg, seed, b, l, int(self.lens[b]))
+                self.seq[b][l] = (q, k, v)
+                qs.append(q); ks.append(k); vs.append(v)
+            self.q.append(np.stack(qs))                       # [Bt, Hq, M, d]
+            self.k.append(np.concatenate(ks, axis=1))         # [Hkv, T, d]
+            self.v.append(np.concatenate(vs, axis=1))
+        self.dtype = kv.KVC_BF16 if cfg.dtype == "bf16" else kv.KVC_F32
+
+    def params(self, **kw):
+        c = self.cfg
+        return kv.KvcParams(c.batch, c.layers, c.hq, c.hkv, c.head_dim, c.window, self.dtype, **kw)
+
+    def oracle(self, **kw):
+        """Oracle result per sequence (list of dicts)."""
+        out = []
+        for b in range(self.cfg.batch):
+            qs = [self.seq[b][l][0] for l in range(self.cfg.layers)]
+            ks = [self.seq[b][l][1] for l in range(self.cfg.layers)]
+            vs = [self.seq[b][l][2] for l in range(self.cfg.layers)]
+            out.append(orc.compress(qs, ks, vs, self.budgets[b], **kw))
+        return out
+
+
+def to_dev(arr: np.ndarray) -> torch.Tensor:
+    """Upload; uint16 arrays are bf16 bit patterns."""
+    if arr.dtype == np.uint16:
+        return torch.from_numpy(arr.view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(arr)).cuda()
+
+
+def to_host_bits(t: torch.Tensor) -> np.ndarray:
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.cpu().numpy()
+
+
+class DeviceWorkload:
+    def __init__(self, w: Workload):
+        self.w = w
+        self.q = [to_dev(x) for x in w.q]
+        self.k = [to_dev(x) for x in w.k]
+        self.v = [to_dev(x) for x in w.v]
+        p = w.params()
+        self.ws_bytes = kv.kvc_workspace_size(p, w.total, int(w.lens.max()) if len(w.lens) else 0)
+        self.ws = torch.empty(max(self.ws_bytes, 256), dtype=torch.uint8, device="cuda")
+
+    def ptrs(self, ts):
+        return [t.data_ptr() for t in ts]
+
+
+def stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def run_compress(dw: DeviceWorkload, **pkw):
+    """kvc_compress with every tap attached; returns host arrays."""
+    w, c = dw.w, dw.w.cfg
+    p = w.params(**pkw)
+    tb = sum(w.budgets)
+    tdtype = torch.bfloat16 if c.dtype == "bf16" else torch.float32
+    k_out = torch.zeros(max(tb, 1) * c.hkv * c.head_dim, dtype=tdtype, device="cuda")
+    v_out = torch.zeros_like(k_out)
+    lengths = torch.full((c.batch * c.layers,), -1, dtype=torch.int32, device="cuda")
+    offsets = torch.full((c.batch * c.layers + 1,), -1, dtype=torch.int64, device="cuda")
+    S = torch.zeros((c.layers, c.hkv, max(w.total, 1)), dtype=torch.float32, device="cuda")
+    idx = torch.zeros((c.layers, c.hkv, max(w.total, 1)), dtype=torch.int32, device="cuda")
+    ss = torch.zeros_like(S)
+    I = torch.zeros((c.layers, max(w.total, 1)), dtype=torch.float32, device="cuda")
+    tau = torch.zeros(c.batch, dtype=torch.float32, device="cuda")
+    kv.kvc_compress(p, dw.ptrs(dw.q), dw.ptrs(dw.k), dw.ptrs(dw.v), w.cu, w.budgets,
+                    k_out.data_ptr(), v_out.data_ptr(), lengths.data_ptr(), offsets.data_ptr(),
+                    dw.ws.data_ptr(), dw.ws_bytes, stream(), scores=S.data_ptr(),
+                    idx=idx.data_ptr(), s_sorted=ss.data_ptr(), composite=I.data_ptr(),
+                    tau=tau.data_ptr())
+    torch.cuda.synchronize()
+    return {
+        "S": S.cpu().numpy(), "idx": idx.cpu().numpy(), "S_sorted": ss.cpu().numpy(),
+        "I": I.cpu().numpy(), "tau": tau.cpu().numpy(),
+        "lengths": lengths.cpu().numpy().reshape(c.batch, c.layers),
+        "offsets": offsets.cpu().numpy(), "k_out": to_host_bits(k_out), "v_out": to_host_bits(v_out),
+    }
+
+
+def check_end_to_end(w: Workload, got: dict, ref: list, eps: float = EPS):
+    """Spec acceptance rules; returns counts of exempted near-threshold tokens."""
+    c = w.cfg
+    exempt = 0
+    off = got["offsets"]
+    assert off[0] == 0
+    for b in range(c.batch):
+        lo, hi = int(w.cu[b]), int(w.cu[b + 1])
+        n = hi - lo
+        r = ref[b]
+        B = w.budgets[b]
+        S_g = got["S"][:, :, lo:hi]
+        np.testing.assert_allclose(S_g, r["S"], rtol=eps, atol=0)
+        lens = got["lengths"][b]
+        assert int(lens.sum()) == B
+        tau = r["tau"]
+        for l in range(c.layers):
+            blk = b * c.layers + l
+            assert off[blk + 1] - off[blk] == lens[l]
+            nl = int(lens[l])
+            if B > 0:
+                lo_ok = int((r["I"][l] > tau * (1 + eps)).sum())
+                hi_ok = int((r["I"][l] >= tau * (1 - eps)).sum())
+                assert lo_ok <= nl <= hi_ok, (b, l, nl, lo_ok, hi_ok)
+            else:
+                assert nl == 0
+            base = int(off[blk]) * c.hkv * c.head_dim
+            kblk = got["k_out"][base: base + c.hkv * nl * c.head_dim].reshape(c.hkv, nl, c.head_dim)
+            vblk = got["v_out"][base: base + c.hkv * nl * c.head_dim].reshape(c.hkv, nl, c.head_dim)
+            k_src, v_src = w.seq[b][l][1], w.seq[b][l][2]
+            for h in range(c.hkv):
+                sel = got["idx"][l, h, lo:lo + nl]
+                assert sel.min(initial=0) >= 0 and sel.max(initial=0) < max(n, 1)
+                assert len(np.unique(sel)) == nl
+                np.testing.assert_array_equal(kblk[h], k_src[h, sel])      # bit-exact copy
+                np.testing.assert_array_equal(vblk[h], v_src[h, sel])
+                if nl == 0:
+                    continue
+                t = r["S_sorted"][l, h, nl - 1]
+                s_o = r["S"][l, h]
+                chosen = np.zeros(n, dtype=bool)
+                chosen[sel] = True
+                must = s_o > t * (1 + eps)
+                must_not = s_o < t * (1 - eps)
+                assert chosen[must].all(), (b, l, h)
+                assert not chosen[must_not].any(), (b, l, h)
+                exempt += int((~must & ~must_not).sum())
+            # full permutation and order of the tap
+            for h in range(c.hkv):
+                full = got["idx"][l, h, lo:hi]
+                assert np.array_equal(np.sort(full), np.arange(n))
+                ssg = got["S_sorted"][l, h, lo:hi]
+                assert np.all(np.diff(ssg) <= 0)
+                np.testing.assert_array_equal(ssg, S_g[l, h, full])
+            assert np.all(np.diff(got["I"][l, lo:hi]) <= 0)
+    assert off[-1] == sum(w.budgets)
+    return exempt

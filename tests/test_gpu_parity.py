@@ -1,0 +1,314 @@
+"""GPU parity: the HIP library (through the C ABI) against the CPU oracle on the
+same seeded inputs.  Stage tests feed each stage the oracle's own intermediates
+(rounded to fp32), so ordering/integer results must be bit-exact; end-to-end
+tests apply the near-threshold exemption rules."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2509_05165_amd as kv
+import workloads as wl
+from oracle import kvc_oracle as orc
+from kvc_testlib import (DeviceWorkload, Workload, check_end_to_end, run_compress, stream,
+                         to_dev, to_host_bits, EPS)
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(f"[case] {msg}", flush=True)
+
+
+# ------------------------------------------------------------------ score
+SCORE_CASES = {
+    # name: (config id, overrides, lens)
+    "tiny-f32": (0, dict(layers=2), None),
+    "f32-gqa-ragged": (0, dict(layers=1, hq=6, hkv=2, n=777, window=20, head_dim=32), None),
+    "bf16-mfma-ragged": (1, dict(layers=2, n=1500), None),
+    "bf16-mfma-multi-chunk": (1, dict(layers=1, n=2600), None),
+    "bf16-mfma-noGQA": (1, dict(layers=1, hq=4, hkv=4, n=700), None),
+    "bf16-mfma-g2-m32": (1, dict(layers=1, hq=8, hkv=4, window=32, n=500), None),
+    "bf16-mfma-g3-m32": (1, dict(layers=1, hq=6, hkv=2, window=32, n=300), None),
+    "bf16-mfma-gqa8-m128": (4, dict(layers=2, n=1100), None),
+    "bf16-generic-d64": (1, dict(layers=1, head_dim=64, hq=8, hkv=4, n=400), None),
+    "bf16-generic-m48": (1, dict(layers=1, window=48, hq=8, hkv=4, n=400), None),
+    "bf16-varlen-batch": (3, dict(layers=1, batch=3, n_range=(200, 1400)), None),
+    "bf16-12-kv-heads": (1, dict(layers=1, hq=24, hkv=12, n=300), None),
+}
+
+
+@pytest.mark.parametrize("name", list(SCORE_CASES))
+def test_score_matches_oracle(name):
+    cid, over, lens = SCORE_CASES[name]
+    _say(f"score {name}")
+    w = Workload(wl.get_config(cid, **over), seed=0, lens=lens)
+    dw = DeviceWorkload(w)
+    c = w.cfg
+    S = torch.zeros((c.layers, c.hkv, w.total), dtype=torch.float32, device="cuda")
+    kv.kvc_score(w.params(), dw.ptrs(dw.q), dw.ptrs(dw.k), w.cu, S.data_ptr(),
+                 dw.ws.data_ptr(), dw.ws_bytes, stream())
+    torch.cuda.synchronize()
+    got = S.cpu().numpy()
+    worst = 0.0
+    for b in range(c.batch):
+        lo, hi = int(w.cu[b]), int(w.cu[b + 1])
+        for l in range(c.layers):
+            ref = orc.score_layer(orc.widen(w.seq[b][l][0]), orc.widen(w.seq[b][l][1]))
+            err = np.abs(got[l, :, lo:hi] - ref) / ref
+            worst = max(worst, float(err.max()))
+    _say(f"score {name}: worst relative error {worst:.3e}")
+    assert worst <= EPS
+    assert worst <= 1e-4, "fp32 pipeline should be far inside the tolerance"
+
+
+@pytest.mark.parametrize("agg_task,agg_group,head_mean", [
+    (kv.KVC_AGG_MEAN, kv.KVC_AGG_MEAN, 1), (kv.KVC_AGG_MAX, kv.KVC_AGG_MAX, 1),
+    (kv.KVC_AGG_MEAN, kv.KVC_AGG_MAX, 0), (kv.KVC_AGG_MAX, kv.KVC_AGG_MEAN, 0)])
+@pytest.mark.parametrize("cid,over", [(0, dict(layers=1, hq=8, hkv=4)),
+                                      (1, dict(layers=1, n=900))])
+def test_score_aggregator_variants(agg_task, agg_group, head_mean, cid, over):
+    _say(f"score variants task={agg_task} group={agg_group} mean={head_mean} cfg={cid}")
+    w = Workload(wl.get_config(cid, **over), seed=1)
+    dw = DeviceWorkload(w)
+    c = w.cfg
+    S = torch.zeros((c.layers, c.hkv, w.total), dtype=torch.float32, device="cuda")
+    p = w.params(agg_task=agg_task, agg_group=agg_group, add_head_mean=head_mean)
+    kv.kvc_score(p, dw.ptrs(dw.q), dw.ptrs(dw.k), w.cu, S.data_ptr(), dw.ws.data_ptr(),
+                 dw.ws_bytes, stream())
+    torch.cuda.synchronize()
+    ref = orc.score_layer(orc.widen(w.seq[0][0][0]), orc.widen(w.seq[0][0][1]),
+                          agg_task=agg_task, agg_group=agg_group, add_head_mean=bool(head_mean))
+    np.testing.assert_allclose(S.cpu().numpy()[0], ref, rtol=1e-4)
+
+
+def test_score_scale_override():
+    w = Workload(wl.get_config(1, layers=1, n=600), seed=2)
+    dw = DeviceWorkload(w)
+    c = w.cfg
+    S = torch.zeros((1, c.hkv, w.total), dtype=torch.float32, device="cuda")
+    kv.kvc_score(w.params(softmax_scale=0.05), dw.ptrs(dw.q), dw.ptrs(dw.k), w.cu, S.data_ptr(),
+                 dw.ws.data_ptr(), dw.ws_bytes, stream())
+    torch.cuda.synchronize()
+    ref = orc.score_layer(orc.widen(w.seq[0][0][0]), orc.widen(w.seq[0][0][1]), scale=0.05)
+    np.testing.assert_allclose(S.cpu().numpy()[0], ref, rtol=1e-4)
+
+
+# ------------------------------------------------------------------ rank / composite
+def _rank_inputs(kind, lyr, hkv, lens, seed):
+    r = np.random.default_rng([77, seed])
+    total = int(sum(lens))
+    if kind == "scores":          # shaped like real scores: tiny positives, a few large
+        s = np.exp(r.standard_normal((lyr, hkv, total)) * 2 - 9).astype(np.float32)
+    elif kind == "ties":          # 9 distinct values
+        s = (np.round(r.random((lyr, hkv, total)) * 8) / 8).astype(np.float32)
+    elif kind == "signed":        # negative values, zeros of both signs, denormals
+        s = r.standard_normal((lyr, hkv, total)).astype(np.float32)
+        s[..., ::7] = 0.0
+        s[..., 3::11] = -0.0
+        s[..., 5::13] = 1e-42
+    elif kind == "constant":
+        s = np.full((lyr, hkv, total), 0.25, dtype=np.float32)
+    return s
+
+
+@pytest.mark.parametrize("kind", ["scores", "ties", "signed", "constant"])
+@pytest.mark.parametrize("lens", [[1], [63], [4096], [4097], [9000, 1, 300], [20000]])
+def test_head_rank_bit_exact(kind, lens):
+    _say(f"rank {kind} lens={lens}")
+    lyr, hkv = 2, 3
+    s = _rank_inputs(kind, lyr, hkv, lens, len(lens))
+    cu = np.concatenate([[0], np.cumsum(lens)])
+    total = int(cu[-1])
+    p = kv.KvcParams(len(lens), lyr, hkv, hkv, 128, 64, kv.KVC_BF16)
+    ws_bytes = kv.kvc_workspace_size(p, total, max(lens))
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    S = to_dev(s)
+    idx = torch.full((lyr, hkv, total), -1, dtype=torch.int32, device="cuda")
+    ss = torch.zeros_like(S)
+    kv.kvc_head_rank(p, S.data_ptr(), cu, idx.data_ptr(), ss.data_ptr(), ws.data_ptr(), ws_bytes,
+                     stream())
+    torch.cuda.synchronize()
+    gi, gs = idx.cpu().numpy(), ss.cpu().numpy()
+    for b in range(len(lens)):
+        lo, hi = int(cu[b]), int(cu[b + 1])
+        ri, rs = orc.head_rank(s[:, :, lo:hi].astype(np.float64))
+        np.testing.assert_array_equal(gi[:, :, lo:hi], ri)
+        np.testing.assert_array_equal(gs[:, :, lo:hi], rs.astype(np.float32))   # -0 == +0
+        assert np.all(np.diff(gs[:, :, lo:hi], axis=-1) <= 0)
+        np.testing.assert_array_equal(gs[:, :, lo:hi], np.take_along_axis(
+            s[:, :, lo:hi], gi[:, :, lo:hi].astype(np.int64), axis=-1))
+
+
+@pytest.mark.parametrize("agg_head", [kv.KVC_AGG_MEAN, kv.KVC_AGG_MAX])
+def test_composite_matches_oracle(agg_head):
+    _say(f"composite agg_head={agg_head}")
+    lyr, hkv, lens = 3, 8, [1000, 37]
+    cu = np.concatenate([[0], np.cumsum(lens)])
+    total = int(cu[-1])
+    r = np.random.default_rng(5)
+    ss = -np.sort(-np.exp(r.standard_normal((lyr, hkv, total)) * 2 - 9), axis=-1).astype(np.float32)
+    p = kv.KvcParams(len(lens), lyr, hkv, hkv, 128, 64, kv.KVC_BF16, agg_head=agg_head)
+    I = torch.zeros((lyr, total), dtype=torch.float32, device="cuda")
+    d_ss = to_dev(ss)
+    kv.kvc_composite(p, d_ss.data_ptr(), cu, I.data_ptr(), stream())
+    torch.cuda.synchronize()
+    got = I.cpu().numpy()
+    for l in range(lyr):
+        ref = orc.composite(ss[l].astype(np.float64), agg_head)
+        if agg_head == kv.KVC_AGG_MAX:
+            np.testing.assert_array_equal(got[l], ref.astype(np.float32))
+        else:
+            np.testing.assert_allclose(got[l], ref, rtol=4 * 2.0 ** -24)   # a few fp32 ulps
+
+
+# ------------------------------------------------------------------ global select
+def _select_case(lyr, lens, budgets, kind, seed):
+    r = np.random.default_rng([88, seed])
+    total = int(sum(lens))
+    if kind == "smooth":
+        i_all = np.exp(r.standard_normal((lyr, total)) * 2 - 9)
+    elif kind == "ties":
+        i_all = np.round(r.random((lyr, total)) * 6) / 8
+    elif kind == "equal-layers":
+        i_all = np.broadcast_to(np.exp(r.standard_normal((1, total)) - 5), (lyr, total)).copy()
+    i_all = i_all.astype(np.float32)
+    cu = np.concatenate([[0], np.cumsum(lens)])
+    for b in range(len(lens)):     # each layer non-increasing inside a sequence
+        lo, hi = int(cu[b]), int(cu[b + 1])
+        i_all[:, lo:hi] = -np.sort(-i_all[:, lo:hi], axis=1)
+    return i_all, cu
+
+
+@pytest.mark.parametrize("kind", ["smooth", "ties", "equal-layers"])
+@pytest.mark.parametrize("lyr,lens,fracs", [
+    (4, [1024], [0.25]), (3, [5000], [0.0]), (3, [5000], [1.0]), (5, [3000, 1, 777], [0.2, 1.0, 0.5]),
+    (32, [4096], [0.1]), (2, [2049, 2048], [0.999, 0.001])])
+def test_global_select_bit_exact(kind, lyr, lens, fracs):
+    _say(f"select {kind} lyr={lyr} lens={lens} fracs={fracs}")
+    i_all, cu = _select_case(lyr, lens, fracs, kind, lyr)
+    budgets = [int(f * lyr * n) for f, n in zip(fracs, lens)]
+    total = int(cu[-1])
+    p = kv.KvcParams(len(lens), lyr, 8, 8, 128, 64, kv.KVC_BF16)
+    ws_bytes = kv.kvc_workspace_size(p, total, max(lens))
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    I = to_dev(i_all)
+    tau = torch.zeros(len(lens), dtype=torch.float32, device="cuda")
+    lengths = torch.full((len(lens) * lyr,), -1, dtype=torch.int32, device="cuda")
+    offsets = torch.full((len(lens) * lyr + 1,), -1, dtype=torch.int64, device="cuda")
+    kv.kvc_global_select(p, I.data_ptr(), cu, budgets, tau.data_ptr(), lengths.data_ptr(),
+                         offsets.data_ptr(), ws.data_ptr(), ws_bytes, stream())
+    torch.cuda.synchronize()
+    gl = lengths.cpu().numpy().reshape(len(lens), lyr)
+    go = offsets.cpu().numpy()
+    gt = tau.cpu().numpy()
+    run = 0
+    for b in range(len(lens)):
+        lo, hi = int(cu[b]), int(cu[b + 1])
+        rl, rt = orc.global_select(i_all[:, lo:hi].astype(np.float64), budgets[b])
+        np.testing.assert_array_equal(gl[b], rl)
+        if budgets[b] > 0:
+            assert np.float32(rt) == gt[b]
+        else:
+            assert np.isinf(gt[b]) and gt[b] > 0
+        for l in range(lyr):
+            assert go[b * lyr + l] == run
+            run += int(rl[l])
+    assert go[-1] == run == sum(budgets)
+
+
+# ------------------------------------------------------------------ gather
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f32", 64), ("bf16", 64), ("f32", 20)])
+def test_gather_bit_exact(dtype, d):
+    _say(f"gather {dtype} d={d}")
+    r = np.random.default_rng(9)
+    lyr, hkv, lens = 3, 4, [700, 33]
+    cu = np.concatenate([[0], np.cumsum(lens)])
+    total = int(cu[-1])
+    if dtype == "bf16":
+        ks = [r.integers(0, 2 ** 16, size=(hkv, total, d)).astype(np.uint16) for _ in range(lyr)]
+        vs = [r.integers(0, 2 ** 16, size=(hkv, total, d)).astype(np.uint16) for _ in range(lyr)]
+    else:
+        ks = [r.standard_normal((hkv, total, d)).astype(np.float32) for _ in range(lyr)]
+        vs = [r.standard_normal((hkv, total, d)).astype(np.float32) for _ in range(lyr)]
+    idx = np.zeros((lyr, hkv, total), dtype=np.int32)
+    for l in range(lyr):
+        for h in range(hkv):
+            for b in range(2):
+                idx[l, h, cu[b]:cu[b + 1]] = r.permutation(lens[b])
+    lengths = np.array([[300, 0, 700], [33, 5, 0]], dtype=np.int32)      # [b][l]
+    offsets = np.concatenate([[0], np.cumsum(lengths.reshape(-1))]).astype(np.int64)
+    tb = int(offsets[-1])
+    p = kv.KvcParams(2, lyr, hkv, hkv, d, 64, kv.KVC_BF16 if dtype == "bf16" else kv.KVC_F32)
+    dk, dv = [to_dev(x) for x in ks], [to_dev(x) for x in vs]
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    k_out = torch.zeros(tb * hkv * d, dtype=tdt, device="cuda")
+    v_out = torch.zeros_like(k_out)
+    d_idx, d_len, d_off = to_dev(idx), to_dev(lengths.reshape(-1)), to_dev(offsets)
+    kv.kvc_gather(p, [t.data_ptr() for t in dk], [t.data_ptr() for t in dv], d_idx.data_ptr(),
+                  d_len.data_ptr(), d_off.data_ptr(), cu, tb, k_out.data_ptr(), v_out.data_ptr(),
+                  stream())
+    torch.cuda.synchronize()
+    gk, gv = to_host_bits(k_out), to_host_bits(v_out)
+    for b in range(2):
+        lo, hi = int(cu[b]), int(cu[b + 1])
+        for l in range(lyr):
+            n = int(lengths[b, l])
+            base = int(offsets[b * lyr + l]) * hkv * d
+            rk = orc.gather(ks[l][:, lo:hi], idx[l, :, lo:hi], n)
+            rv = orc.gather(vs[l][:, lo:hi], idx[l, :, lo:hi], n)
+            np.testing.assert_array_equal(gk[base: base + hkv * n * d].reshape(hkv, n, d), rk)
+            np.testing.assert_array_equal(gv[base: base + hkv * n * d].reshape(hkv, n, d), rv)
+
+
+# ------------------------------------------------------------------ whole pass
+E2E_CASES = {
+    "config0-tiny": (0, {}, None),
+    "config1-small": (1, dict(layers=4, n=3000), None),
+    "config3-varlen-small": (3, dict(layers=3, batch=4, n_range=(300, 2500)), None),
+    "config4-small": (4, dict(layers=5, n=1500), None),
+}
+
+
+@pytest.mark.parametrize("name", list(E2E_CASES))
+def test_compress_end_to_end(name):
+    cid, over, lens = E2E_CASES[name]
+    _say(f"e2e {name}")
+    w = Workload(wl.get_config(cid, **over), seed=0, lens=lens)
+    dw = DeviceWorkload(w)
+    got = run_compress(dw)
+    ref = w.oracle()
+    exempt = check_end_to_end(w, got, ref)
+    _say(f"e2e {name}: exempt near-threshold tokens = {exempt}")
+    again = run_compress(dw)                          # determinism: bitwise identical rerun
+    for key in got:
+        np.testing.assert_array_equal(got[key], again[key])
+
+
+@pytest.mark.parametrize("keep", [0, 100])
+def test_compress_budget_extremes(keep):
+    _say(f"e2e budget {keep}%")
+    w = Workload(wl.get_config(1, layers=2, n=900, keep_percent=keep), seed=3)
+    got = run_compress(DeviceWorkload(w))
+    ref = w.oracle()
+    check_end_to_end(w, got, ref)
+    assert (got["lengths"] == (900 if keep == 100 else 0)).all()
+
+
+def test_batch_packing_independence():
+    _say("e2e packing independence")
+    cfg = wl.get_config(3, layers=2, batch=3, n_range=(400, 1200))
+    w = Workload(cfg, seed=4)
+    packed = run_compress(DeviceWorkload(w))
+    b = 1
+    solo_cfg = wl.get_config(3, layers=2, batch=1, n_range=(400, 1200))
+    solo = Workload(solo_cfg, seed=4, lens=[w.lens[b]], budgets=[w.budgets[b]])
+    # same tensors as sequence b of the packed batch
+    for l in range(2):
+        q, k, v = w.seq[b][l]
+        solo.seq[0][l] = (q, k, v)
+        solo.q[l], solo.k[l], solo.v[l] = q[None], k, v
+    alone = run_compress(DeviceWorkload(solo))
+    lo, hi = int(w.cu[b]), int(w.cu[b + 1])
+    np.testing.assert_array_equal(packed["S"][:, :, lo:hi], alone["S"])
+    np.testing.assert_array_equal(packed["idx"][:, :, lo:hi], alone["idx"])
+    np.testing.assert_array_equal(packed["lengths"][b], alone["lengths"][0])
