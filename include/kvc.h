@@ -192,6 +192,22 @@ kvc_status kvc_compress(const kvc_params* params, const kvc_inputs* in,
                         const kvc_outputs* out, void* workspace,
                         size_t workspace_bytes, void* stream);
 
+/* ---- optional per-kernel timing (measurement aid, not part of the pass) ----
+ * While enabled, every kernel the library launches on the calling thread is
+ * bracketed by a pair of HIP events recorded on the launch stream.
+ * kvc_profile_collect synchronises those events, sums the elapsed time per
+ * kernel name into `out` (at most `capacity` entries, in first-launch order),
+ * forgets them and returns the number of distinct names (or -1 on a HIP
+ * error).  Enabling allocates host-side event objects only; it slightly
+ * serialises back-to-back launches, so throughput is timed with it off. */
+typedef struct kvc_profile_entry {
+  char name[48];
+  int32_t launches;
+  float total_ms;
+} kvc_profile_entry;
+void kvc_profile_enable(int on);
+int kvc_profile_collect(kvc_profile_entry* out, int capacity);
+
 #ifdef __cplusplus
 }
 #endif

@@ -179,3 +179,26 @@ def kvc_compress(params, q, k, v, cu_seqlens, budget, k_out, v_out, lengths, off
                                tau)])
     _check(lib().kvc_compress(C.byref(params), C.byref(inp), C.byref(out), _vp(workspace),
                               workspace_bytes, _vp(stream)), "kvc_compress")
+
+
+class _ProfileEntry(C.Structure):
+    _fields_ = [("name", C.c_char * 48), ("launches", C.c_int32), ("total_ms", C.c_float)]
+
+
+def kvc_profile_enable(on: bool) -> None:
+    lib().kvc_profile_enable.argtypes = [C.c_int]
+    lib().kvc_profile_enable.restype = None
+    lib().kvc_profile_enable(1 if on else 0)
+
+
+def kvc_profile_collect(capacity: int = 64):
+    """Returns {kernel name: (launches, total_ms)} for the launches since the
+    last collect (HIP events recorded by the library on the launch stream)."""
+    fn = lib().kvc_profile_collect
+    fn.argtypes = [C.POINTER(_ProfileEntry), C.c_int]
+    fn.restype = C.c_int
+    buf = (_ProfileEntry * capacity)()
+    n = fn(buf, capacity)
+    if n < 0:
+        raise KvcError(4, "kvc_profile_collect", "HIP event query failed")
+    return {buf[i].name.decode(): (buf[i].launches, buf[i].total_ms) for i in range(min(n, capacity))}

@@ -5,6 +5,8 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <string>
+#include <vector>
 
 #include "kvc_internal.h"
 
@@ -22,6 +24,24 @@ void set_error(const char* fmt, ...) {
 kvc_status hip_fail(hipError_t e, const char* what) {
   set_error("%s: %s", what, hipGetErrorString(e));
   return KVC_ERR_HIP;
+}
+
+// ---- per-kernel timing records (thread local, host objects only) ----
+struct ProfRec { const char* name; hipEvent_t start, stop; };
+static thread_local bool g_prof_on = false;
+static thread_local std::vector<ProfRec> g_prof;
+
+void prof_begin(const char* name, hipStream_t stream) {
+  if (!g_prof_on) return;
+  ProfRec r{name, nullptr, nullptr};
+  if (hipEventCreate(&r.start) != hipSuccess || hipEventCreate(&r.stop) != hipSuccess) return;
+  hipEventRecord(r.start, stream);
+  g_prof.push_back(r);
+}
+
+void prof_end(hipStream_t stream) {
+  if (!g_prof_on || g_prof.empty()) return;
+  hipEventRecord(g_prof.back().stop, stream);
 }
 
 static kvc_status check_params(const kvc_params* p) {
@@ -173,6 +193,35 @@ const char* kvc_status_string(int status) {
 }
 
 const char* kvc_last_error(void) { return g_err; }
+
+void kvc_profile_enable(int on) { g_prof_on = on != 0; }
+
+int kvc_profile_collect(kvc_profile_entry* out, int capacity) {
+  int count = 0;
+  bool failed = false;
+  for (ProfRec& r : g_prof) {
+    float ms = 0.f;
+    if (hipEventSynchronize(r.stop) != hipSuccess ||
+        hipEventElapsedTime(&ms, r.start, r.stop) != hipSuccess)
+      failed = true;
+    hipEventDestroy(r.start);
+    hipEventDestroy(r.stop);
+    int slot = -1;
+    for (int i = 0; i < count && i < capacity; ++i)
+      if (std::strncmp(out[i].name, r.name, sizeof(out[i].name) - 1) == 0) { slot = i; break; }
+    if (slot < 0) {
+      if (count < capacity && out) {
+        std::memset(&out[count], 0, sizeof(out[count]));
+        std::strncpy(out[count].name, r.name, sizeof(out[count].name) - 1);
+        slot = count;
+      }
+      ++count;
+    }
+    if (slot >= 0 && slot < capacity && out) { out[slot].launches += 1; out[slot].total_ms += ms; }
+  }
+  g_prof.clear();
+  return failed ? -1 : count;
+}
 
 int64_t kvc_budget(int32_t keep_percent, int32_t layers, int64_t n) {
   if (keep_percent < 0 || keep_percent > 100 || layers < 0 || n < 0) return -1;

@@ -63,10 +63,9 @@ kvc_status launch_gather(const Problem& pb, const void* const* k, const void* co
   int64_t blocks = (pool_rows + rows_per_block - 1) / rows_per_block;
   const int64_t cap = 256 * 64;
   if (blocks > cap) blocks = cap;
-  gather_kernel<<<(unsigned)blocks, GA_THREADS, 0, stream>>>(
+  KVC_LAUNCH("gather_kernel", stream, gather_kernel<<<(unsigned)blocks, GA_THREADS, 0, stream>>>(
       kt, vt, v != nullptr, idx, lengths, offsets, pb.seq, pb.layers, pb.hkv, int(pb.total),
-      pieces, pool_rows, static_cast<uint4*>(k_out), static_cast<uint4*>(v_out));
-  KVC_HIP_LAUNCH_CHECK("gather_kernel");
+      pieces, pool_rows, static_cast<uint4*>(k_out), static_cast<uint4*>(v_out)));
   return KVC_OK;
 }
 

@@ -35,10 +35,20 @@ inline int esize(int dtype) { return dtype == KVC_BF16 ? 2 : 4; }
 void set_error(const char* fmt, ...);
 kvc_status hip_fail(hipError_t e, const char* what);
 
-#define KVC_HIP_LAUNCH_CHECK(what)                        \
-  do {                                                    \
-    hipError_t e__ = hipGetLastError();                   \
-    if (e__ != hipSuccess) return kvc::hip_fail(e__, what); \
+// Optional event pair around a launch (see kvc_profile_enable).
+void prof_begin(const char* name, hipStream_t stream);
+void prof_end(hipStream_t stream);
+
+// Launch a kernel (the variadic part is the launch expression), bracket it
+// with timing events when profiling is on, and turn a launch failure into
+// KVC_ERR_HIP.
+#define KVC_LAUNCH(name, stream, ...)                       \
+  do {                                                      \
+    kvc::prof_begin(name, stream);                          \
+    __VA_ARGS__;                                            \
+    kvc::prof_end(stream);                                  \
+    hipError_t e__ = hipGetLastError();                     \
+    if (e__ != hipSuccess) return kvc::hip_fail(e__, name); \
   } while (0)
 
 // ---------------------------------------------------------------------------

@@ -199,18 +199,16 @@ kvc_status launch_head_rank(const Problem& pb, const float* S, int32_t* idx, flo
   uint32_t* tmp_keys = static_cast<uint32_t*>(ws);
   int32_t* tmp_idx = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + align_up(lht * 4));
   dim3 grid(pb.layers * pb.hkv, pb.batch);
-  head_rank_kernel<<<grid, RK_THREADS, 0, stream>>>(S, pb.seq, int(pb.total), idx, S_sorted,
-                                                    tmp_keys, tmp_idx);
-  KVC_HIP_LAUNCH_CHECK("head_rank_kernel");
+  KVC_LAUNCH("head_rank_kernel", stream, head_rank_kernel<<<grid, RK_THREADS, 0, stream>>>(S, pb.seq, int(pb.total), idx, S_sorted,
+                                                    tmp_keys, tmp_idx));
   return KVC_OK;
 }
 
 kvc_status launch_composite(const Problem& pb, const float* S_sorted, float* I,
                             hipStream_t stream) {
   dim3 grid((unsigned)((pb.total + 255) / 256), pb.layers);
-  composite_kernel<<<grid, 256, 0, stream>>>(S_sorted, pb.hkv, int(pb.total),
-                                             pb.agg_head == KVC_AGG_MAX, I);
-  KVC_HIP_LAUNCH_CHECK("composite_kernel");
+  KVC_LAUNCH("composite_kernel", stream, composite_kernel<<<grid, 256, 0, stream>>>(S_sorted, pb.hkv, int(pb.total),
+                                             pb.agg_head == KVC_AGG_MAX, I));
   return KVC_OK;
 }
 

@@ -517,22 +517,20 @@ kvc_status launch_score(const Problem& pb, const void* const* q, const void* con
       const uint16_t* ql = static_cast<const uint16_t*>(q[l]);
       const uint16_t* kl = static_cast<const uint16_t*>(k[l]);
       dim3 grid(chunks, pb.hkv * L.row_chunks, pb.batch);
-      score_mfma<false, true><<<grid, 256, 0, stream>>>(
+      KVC_LAUNCH("score_mfma<stats>", stream, score_mfma<false, true><<<grid, 256, 0, stream>>>(
           ql, kl, pb.seq, pb.hq, pb.group, pb.window, total, c2, chunk, L.max_chunks,
-          L.row_chunks, part_m, part_s, nullptr, group_max, nullptr);
-      KVC_HIP_LAUNCH_CHECK("score_mfma<stats>");
-      score_merge<<<(L.rows_layer + 255) / 256, 256, 0, stream>>>(
-          pb.seq, rows_per_seq, chunk, L.max_chunks, part_m, part_s, lse2);
-      KVC_HIP_LAUNCH_CHECK("score_merge");
-      if (task_max)
-        score_mfma<true, true><<<grid, 256, 0, stream>>>(
+          L.row_chunks, part_m, part_s, nullptr, group_max, nullptr));
+      KVC_LAUNCH("score_merge", stream, score_merge<<<(L.rows_layer + 255) / 256, 256, 0, stream>>>(
+          pb.seq, rows_per_seq, chunk, L.max_chunks, part_m, part_s, lse2));
+      if (task_max) {
+        KVC_LAUNCH("score_mfma<emit>", stream, score_mfma<true, true><<<grid, 256, 0, stream>>>(
             ql, kl, pb.seq, pb.hq, pb.group, pb.window, total, c2, chunk, L.max_chunks,
-            L.row_chunks, nullptr, nullptr, lse2, group_max, part);
-      else
-        score_mfma<true, false><<<grid, 256, 0, stream>>>(
+            L.row_chunks, nullptr, nullptr, lse2, group_max, part));
+      } else {
+        KVC_LAUNCH("score_mfma<emit>", stream, score_mfma<true, false><<<grid, 256, 0, stream>>>(
             ql, kl, pb.seq, pb.hq, pb.group, pb.window, total, c2, chunk, L.max_chunks,
-            L.row_chunks, nullptr, nullptr, lse2, group_max, part);
-      KVC_HIP_LAUNCH_CHECK("score_mfma<emit>");
+            L.row_chunks, nullptr, nullptr, lse2, group_max, part));
+      }
     } else {
       const int row_blocks = (pb.window + GEN_RB - 1) / GEN_RB;
       dim3 gs(chunks, pb.hq * row_blocks, pb.batch), ge(chunks, pb.hkv, pb.batch);
@@ -541,37 +539,30 @@ kvc_status launch_score(const Problem& pb, const void* const* q, const void* con
       if (pb.dtype == KVC_BF16) {
         const uint16_t* ql = static_cast<const uint16_t*>(q[l]);
         const uint16_t* kl = static_cast<const uint16_t*>(k[l]);
-        score_stats_generic<uint16_t><<<gs, 256, lds_s, stream>>>(
+        KVC_LAUNCH("score_stats_generic", stream, score_stats_generic<uint16_t><<<gs, 256, lds_s, stream>>>(
             ql, kl, pb.seq, pb.hq, pb.group, pb.window, pb.d, total, c2, chunk, L.max_chunks,
-            part_m, part_s);
-        KVC_HIP_LAUNCH_CHECK("score_stats_generic");
-        score_merge<<<(L.rows_layer + 255) / 256, 256, 0, stream>>>(
-            pb.seq, rows_per_seq, chunk, L.max_chunks, part_m, part_s, lse2);
-        KVC_HIP_LAUNCH_CHECK("score_merge");
-        score_emit_generic<uint16_t><<<ge, 256, lds_e, stream>>>(
+            part_m, part_s));
+        KVC_LAUNCH("score_merge", stream, score_merge<<<(L.rows_layer + 255) / 256, 256, 0, stream>>>(
+            pb.seq, rows_per_seq, chunk, L.max_chunks, part_m, part_s, lse2));
+        KVC_LAUNCH("score_emit_generic", stream, score_emit_generic<uint16_t><<<ge, 256, lds_e, stream>>>(
             ql, kl, pb.seq, pb.hq, pb.group, pb.window, pb.d, total, c2, chunk, lse2, task_max,
-            group_max, part);
-        KVC_HIP_LAUNCH_CHECK("score_emit_generic");
+            group_max, part));
       } else {
         const float* ql = static_cast<const float*>(q[l]);
         const float* kl = static_cast<const float*>(k[l]);
-        score_stats_generic<float><<<gs, 256, lds_s, stream>>>(
+        KVC_LAUNCH("score_stats_generic", stream, score_stats_generic<float><<<gs, 256, lds_s, stream>>>(
             ql, kl, pb.seq, pb.hq, pb.group, pb.window, pb.d, total, c2, chunk, L.max_chunks,
-            part_m, part_s);
-        KVC_HIP_LAUNCH_CHECK("score_stats_generic");
-        score_merge<<<(L.rows_layer + 255) / 256, 256, 0, stream>>>(
-            pb.seq, rows_per_seq, chunk, L.max_chunks, part_m, part_s, lse2);
-        KVC_HIP_LAUNCH_CHECK("score_merge");
-        score_emit_generic<float><<<ge, 256, lds_e, stream>>>(
+            part_m, part_s));
+        KVC_LAUNCH("score_merge", stream, score_merge<<<(L.rows_layer + 255) / 256, 256, 0, stream>>>(
+            pb.seq, rows_per_seq, chunk, L.max_chunks, part_m, part_s, lse2));
+        KVC_LAUNCH("score_emit_generic", stream, score_emit_generic<float><<<ge, 256, lds_e, stream>>>(
             ql, kl, pb.seq, pb.hq, pb.group, pb.window, pb.d, total, c2, chunk, lse2, task_max,
-            group_max, part);
-        KVC_HIP_LAUNCH_CHECK("score_emit_generic");
+            group_max, part));
       }
     }
-    score_finish<<<(total + 255) / 256, 256, 0, stream>>>(part, L.row_chunks, pb.hkv, total,
+    KVC_LAUNCH("score_finish", stream, score_finish<<<(total + 255) / 256, 256, 0, stream>>>(part, L.row_chunks, pb.hkv, total,
                                                           group_norm, group_max,
-                                                          pb.add_head_mean, S_l);
-    KVC_HIP_LAUNCH_CHECK("score_finish");
+                                                          pb.add_head_mean, S_l));
   }
   return KVC_OK;
 }

@@ -192,22 +192,17 @@ kvc_status launch_global_select(const Problem& pb, const float* I, const int64_t
   for (int b = 0; b < pb.batch; ++b) bt.b[b] = budget[b];
   const int total = int(pb.total);
 
-  select_init<<<(L.words + 255) / 256, 256, 0, stream>>>(hist, L.words, state, bt, pb.batch);
-  KVC_HIP_LAUNCH_CHECK("select_init");
+  KVC_LAUNCH("select_init", stream, select_init<<<(L.words + 255) / 256, 256, 0, stream>>>(hist, L.words, state, bt, pb.batch));
   if (pb.max_seqlen > 0) {
     dim3 grid((unsigned)((pb.max_seqlen + SEL_PER_BLOCK - 1) / SEL_PER_BLOCK), pb.layers, pb.batch);
     for (int pass = 0; pass < 3; ++pass) {
-      select_hist<<<grid, SEL_THREADS, 0, stream>>>(I, pb.seq, total, pass, state, hist);
-      KVC_HIP_LAUNCH_CHECK("select_hist");
-      select_find<<<pb.batch, SEL_THREADS, 0, stream>>>(pass, hist, state);
-      KVC_HIP_LAUNCH_CHECK("select_find");
+      KVC_LAUNCH("select_hist", stream, select_hist<<<grid, SEL_THREADS, 0, stream>>>(I, pb.seq, total, pass, state, hist));
+      KVC_LAUNCH("select_find", stream, select_find<<<pb.batch, SEL_THREADS, 0, stream>>>(pass, hist, state));
     }
-    select_count<<<grid, SEL_THREADS, 0, stream>>>(I, pb.seq, total, pb.layers, state, counts);
-    KVC_HIP_LAUNCH_CHECK("select_count");
+    KVC_LAUNCH("select_count", stream, select_count<<<grid, SEL_THREADS, 0, stream>>>(I, pb.seq, total, pb.layers, state, counts));
   }
-  select_finalize<<<1, 64, 0, stream>>>(pb.seq, pb.layers, bt, state, counts, tau, lengths,
-                                        offsets);
-  KVC_HIP_LAUNCH_CHECK("select_finalize");
+  KVC_LAUNCH("select_finalize", stream, select_finalize<<<1, 64, 0, stream>>>(pb.seq, pb.layers, bt, state, counts, tau, lengths,
+                                        offsets));
   return KVC_OK;
 }
 
