@@ -26,6 +26,14 @@ __device__ __forceinline__ float load_as_float(const uint16_t* p) {
   return __uint_as_float(uint32_t(*p) << 16);
 }
 
+}  // namespace
+}  // namespace kvc
+
+#include "kvc_score_mfma.h"
+
+namespace kvc {
+namespace {
+
 // ---------------------------------------------------------------------------
 // Plain fp32 path
 // ---------------------------------------------------------------------------
@@ -101,8 +109,9 @@ __global__ __launch_bounds__(256) void score_stats_generic(
     const int m = rb * GEN_RB + i * GEN_MGROUPS + mg;
     if (kc == 0 && m < window) {
       const size_t row = ((size_t)b * hq + qh) * window + m;
-      part_m[row * max_chunks + blockIdx.x] = mm;
-      part_s[row * max_chunks + blockIdx.x] = ss;
+      const size_t rows_layer = (size_t)gridDim.z * hq * window;
+      part_m[(size_t)blockIdx.x * rows_layer + row] = mm;
+      part_s[(size_t)blockIdx.x * rows_layer + row] = ss;
     }
   }
 }
@@ -165,24 +174,44 @@ __global__ __launch_bounds__(256) void score_emit_generic(
 }
 
 // ---------------------------------------------------------------------------
-// lse merge: one thread per query row of the layer
+// lse merge: 16 query rows per workgroup, 16 threads per row stride over the
+// key chunks (partials are stored [chunk][row], so reads are coalesced).
 // ---------------------------------------------------------------------------
-__global__ void score_merge(SeqTable seq, int rows_per_seq, int chunk_keys, int max_chunks,
-                            const float* __restrict__ part_m, const float* __restrict__ part_s,
-                            float* __restrict__ lse2) {
-  const int row = blockIdx.x * blockDim.x + threadIdx.x;
-  if (row >= rows_per_seq * seq.batch) return;
-  const int b = row / rows_per_seq;
-  const int n = seq.cu[b + 1] - seq.cu[b];
-  const int chunks = (n + chunk_keys - 1) / chunk_keys;
-  if (chunks == 0) return;
-  const float* pm = part_m + (size_t)row * max_chunks;
-  const float* ps = part_s + (size_t)row * max_chunks;
-  float mm = NEG_BIG;
-  for (int c = 0; c < chunks; ++c) mm = fmaxf(mm, pm[c]);
-  float ss = 0.f;
-  for (int c = 0; c < chunks; ++c) ss += ps[c] * fast_exp2(pm[c] - mm);
-  lse2[row] = mm + __log2f(ss);
+constexpr int MERGE_ROWS = 16;
+
+__global__ __launch_bounds__(256) void score_merge(SeqTable seq, int rows_per_seq, int chunk_keys,
+                                                   const float* __restrict__ part_m,
+                                                   const float* __restrict__ part_s,
+                                                   float* __restrict__ lse2) {
+  __shared__ float sm[16][MERGE_ROWS], ss[16][MERGE_ROWS];
+  const int r = threadIdx.x & (MERGE_ROWS - 1), cg = threadIdx.x >> 4;
+  const int rows = rows_per_seq * seq.batch;
+  const int row = blockIdx.x * MERGE_ROWS + r;
+  float mm = NEG_BIG, acc = 0.f;
+  int chunks = 0;
+  if (row < rows) {
+    const int b = row / rows_per_seq;
+    const int n = seq.cu[b + 1] - seq.cu[b];
+    chunks = (n + chunk_keys - 1) / chunk_keys;
+    for (int c = cg; c < chunks; c += 16) {
+      const float m2 = part_m[(size_t)c * rows + row], s2 = part_s[(size_t)c * rows + row];
+      const float mn = fmaxf(mm, m2);
+      acc = acc * fast_exp2(mm - mn) + s2 * fast_exp2(m2 - mn);
+      mm = mn;
+    }
+  }
+  sm[cg][r] = mm;
+  ss[cg][r] = acc;
+  __syncthreads();
+  if (cg == 0 && row < rows && chunks > 0) {
+    float top = NEG_BIG;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) top = fmaxf(top, sm[i][r]);
+    float tot = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) tot += ss[i][r] * fast_exp2(sm[i][r] - top);
+    lse2[row] = top + __log2f(tot);
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -226,240 +255,6 @@ __global__ void score_finish(const float* part, int row_chunks, int hkv, int tot
   }
 }
 
-// ---------------------------------------------------------------------------
-// bf16 matrix-core path (d = 128, window a multiple of 32 that divides 256)
-// ---------------------------------------------------------------------------
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-
-constexpr int MF_D = 128;
-constexpr int MF_TILE = 128;                 // keys per LDS macro tile
-constexpr int MF_ROWB = MF_D * 2 + 16;       // padded LDS row: 272 bytes
-constexpr int MF_RCHUNK = 256;               // query rows per workgroup
-constexpr int MF_KBUF = MF_TILE * MF_ROWB;   // bytes per K buffer
-
-__device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
-
-// row i of a 32x32 accumulator held in register r of lane l: 8*(r/4) + 4*(l/32) + r%4
-__device__ __forceinline__ int acc_row(int r, int half) { return 8 * (r >> 2) + 4 * half + (r & 3); }
-
-// grid: (chunks, Hkv * row_chunks, Bt), 256 threads.
-template <bool EMIT, bool TASK_MAX>
-__global__ __launch_bounds__(256, 2) void score_mfma(
-    const uint16_t* __restrict__ q_layer, const uint16_t* __restrict__ k_layer, SeqTable seq,
-    int hq, int group, int window, int total, float c2, int chunk_keys, int max_chunks,
-    int row_chunks, float* __restrict__ part_m, float* __restrict__ part_s,
-    const float* __restrict__ lse2, int group_max, float* __restrict__ out) {
-  __shared__ __attribute__((aligned(16))) unsigned char kbuf[2 * MF_KBUF];
-  __shared__ float red[2][8][MF_TILE];       // EMIT: per (q block, key) task aggregate
-  __shared__ float stat[4][2][32][2];        // STATS: per wave (m, s)
-
-  const int b = blockIdx.z;
-  const int tok0 = seq.cu[b], n = seq.cu[b + 1] - tok0;
-  const int key_begin = blockIdx.x * chunk_keys;
-  if (key_begin >= n) return;
-  const int key_end = min(n, key_begin + chunk_keys);
-  const int h = blockIdx.y / row_chunks, rc = blockIdx.y - h * row_chunks;
-  const int R = group * window;
-  const int row0 = rc * MF_RCHUNK;
-  const int nqb = (min(R, row0 + MF_RCHUNK) - row0) / 32;   // q blocks in this row chunk
-  const int WQ = (nqb + 1) / 2;
-  const int WK = 4 / WQ;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int wq = wave % WQ, wk = wave / WQ;
-  const bool active = wk < WK;
-  const int col = lane & 31, half = lane >> 5;
-
-  const uint16_t* k_head = k_layer + (size_t)h * total * MF_D;
-
-  // ---- query fragments (registers, whole kernel) ----
-  uint4 qf[2][8];
-  int grow[2];          // global stats row of this lane's query (column role)
-#pragma unroll
-  for (int qb = 0; qb < 2; ++qb) {
-    const int blk = wq * 2 + qb;
-    const int r = row0 + blk * 32 + col;
-    const bool ok = active && blk < nqb;
-    const int g = ok ? r / window : 0, m = ok ? r % window : 0;
-    const size_t qrow = ((size_t)b * hq + h * group + g) * window + m;
-    grow[qb] = ok ? (int)qrow : -1;
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (ok) v = *reinterpret_cast<const uint4*>(q_layer + qrow * MF_D + ks * 16 + half * 8);
-      qf[qb][ks] = v;
-    }
-  }
-
-  // EMIT: lse2 of the 16 accumulator rows of each q block held by this lane
-  float lrow[2][16];
-  if (EMIT) {
-#pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-      const int blk = wq * 2 + qb;
-      const bool ok = active && blk < nqb;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float v = 0.f;
-        if (ok) {
-          const int rr = row0 + blk * 32 + acc_row(r, half);
-          v = lse2[((size_t)b * hq + h * group + rr / window) * window + rr % window];
-        }
-        lrow[qb][r] = v;
-      }
-    }
-  }
-
-  float mrun[2] = {NEG_BIG, NEG_BIG}, srun[2] = {0.f, 0.f};
-
-  // ---- K macro tiles through LDS, register-staged double buffering ----
-  uint4 stage[8];
-  auto gload = [&](int key0) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int id = i * 256 + threadIdx.x;
-      const int r = id >> 4, c = id & 15;
-      const int key = min(key0 + r, n - 1);
-      stage[i] = *reinterpret_cast<const uint4*>(k_head + (size_t)(tok0 + key) * MF_D + c * 8);
-    }
-  };
-  auto lstore = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int id = i * 256 + threadIdx.x;
-      const int r = id >> 4, c = id & 15;
-      *reinterpret_cast<uint4*>(kbuf + buf * MF_KBUF + r * MF_ROWB + c * 16) = stage[i];
-    }
-  };
-
-  gload(key_begin);
-  lstore(0);
-  __syncthreads();
-
-  int it = 0;
-  for (int key0 = key_begin; key0 < key_end; key0 += MF_TILE, ++it) {
-    const int cur = it & 1;
-    const bool more = key0 + MF_TILE < key_end;
-    if (more) gload(key0 + MF_TILE);
-
-    if (active) {
-      const unsigned char* kb = kbuf + cur * MF_KBUF;
-      for (int kt = wk; kt < MF_TILE / 32; kt += WK) {
-        const int tkey0 = key0 + kt * 32;
-        if (tkey0 >= key_end) break;
-        f32x16 acc[2];
-#pragma unroll
-        for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) acc[qb][r] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-          const uint4 kv = *reinterpret_cast<const uint4*>(kb + (kt * 32 + col) * MF_ROWB +
-                                                           (2 * ks + half) * 16);
-          const bf16x8 kf = as_bf16x8(kv);
-#pragma unroll
-          for (int qb = 0; qb < 2; ++qb) {
-            if (EMIT)   // rows = queries, columns = keys
-              acc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(qf[qb][ks]), kf, acc[qb], 0, 0, 0);
-            else        // rows = keys, columns = queries
-              acc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, as_bf16x8(qf[qb][ks]), acc[qb], 0, 0, 0);
-          }
-        }
-        if (!EMIT) {
-          const bool ragged = tkey0 + 32 > key_end;
-#pragma unroll
-          for (int qb = 0; qb < 2; ++qb) {
-            float t[16];
-            float tmax = NEG_BIG;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-              t[r] = acc[qb][r] * c2;
-              if (ragged && tkey0 + acc_row(r, half) >= key_end) t[r] = NEG_BIG;
-              tmax = fmaxf(tmax, t[r]);
-            }
-            const float mn = fmaxf(mrun[qb], tmax);
-            float s = srun[qb] * fast_exp2(mrun[qb] - mn);
-#pragma unroll
-            for (int r = 0; r < 16; ++r) s += fast_exp2(t[r] - mn);
-            srun[qb] = s;
-            mrun[qb] = mn;
-          }
-        } else {
-#pragma unroll
-          for (int qb = 0; qb < 2; ++qb) {
-            float v = TASK_MAX ? NEG_BIG : 0.f;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-              const float t = acc[qb][r] * c2 - lrow[qb][r];
-              v = TASK_MAX ? fmaxf(v, t) : v + fast_exp2(t);
-            }
-            const float o = __shfl_xor(v, 32);
-            v = TASK_MAX ? fmaxf(v, o) : v + o;
-            const int blk = wq * 2 + qb;
-            if (half == 0 && blk < nqb) red[cur][blk][kt * 32 + col] = v;
-          }
-        }
-      }
-    }
-
-    if (more) lstore(cur ^ 1);
-    __syncthreads();
-
-    if (EMIT) {
-      // threads 0..127: one key each; combine q blocks -> task -> group
-      const int key = key0 + (int)threadIdx.x;
-      if (threadIdx.x < MF_TILE && key < key_end) {
-        const int bpg = window / 32;            // q blocks per query head
-        const int gcount = nqb / bpg;           // query heads in this row chunk
-        float gacc = 0.f;
-        for (int g = 0; g < gcount; ++g) {
-          float tv = TASK_MAX ? NEG_BIG : 0.f;
-          for (int j = 0; j < bpg; ++j) {
-            const float x = red[cur][g * bpg + j][threadIdx.x];
-            tv = TASK_MAX ? fmaxf(tv, x) : tv + x;
-          }
-          const float sv = TASK_MAX ? fast_exp2(tv) : tv / float(window);
-          gacc = group_max ? fmaxf(gacc, sv) : gacc + sv;
-        }
-        out[((size_t)rc * (gridDim.y / row_chunks) + h) * total + tok0 + key] = gacc;
-      }
-    }
-  }
-
-  if (!EMIT) {
-    // lanes l and l+32 hold the same query over different keys
-#pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-      const float m2 = __shfl_xor(mrun[qb], 32), s2 = __shfl_xor(srun[qb], 32);
-      const float mn = fmaxf(mrun[qb], m2);
-      srun[qb] = srun[qb] * fast_exp2(mrun[qb] - mn) + s2 * fast_exp2(m2 - mn);
-      mrun[qb] = mn;
-      if (half == 0) { stat[wave][qb][col][0] = mrun[qb]; stat[wave][qb][col][1] = srun[qb]; }
-    }
-    __syncthreads();
-    // one thread per query row of the row chunk merges the WK key-split waves
-    const int t = threadIdx.x;
-    if (t < nqb * 32) {
-      const int blk = t >> 5, j = t & 31;
-      const int sq = blk >> 1, qb = blk & 1;
-      float mm = NEG_BIG;
-      for (int k2 = 0; k2 < WK; ++k2) mm = fmaxf(mm, stat[k2 * WQ + sq][qb][j][0]);
-      float ss = 0.f;
-      for (int k2 = 0; k2 < WK; ++k2)
-        ss += stat[k2 * WQ + sq][qb][j][1] * fast_exp2(stat[k2 * WQ + sq][qb][j][0] - mm);
-      const int r = row0 + blk * 32 + j;
-      const size_t qrow = ((size_t)b * hq + h * group + r / window) * window + r % window;
-      part_m[qrow * max_chunks + blockIdx.x] = mm;
-      part_s[qrow * max_chunks + blockIdx.x] = ss;
-    }
-  }
-  (void)grow;
-}
-
-inline bool mfma_supported(const Problem& pb) {
-  return pb.dtype == KVC_BF16 && pb.d == MF_D && pb.window % 32 == 0 && pb.window <= MF_RCHUNK &&
-         MF_RCHUNK % pb.window == 0;
-}
 
 constexpr int GEN_CHUNK = 256;
 constexpr int MF_CHUNK = 1024;
@@ -517,20 +312,27 @@ kvc_status launch_score(const Problem& pb, const void* const* q, const void* con
       const uint16_t* ql = static_cast<const uint16_t*>(q[l]);
       const uint16_t* kl = static_cast<const uint16_t*>(k[l]);
       dim3 grid(chunks, pb.hkv * L.row_chunks, pb.batch);
-      KVC_LAUNCH("score_mfma<stats>", stream, score_mfma<false, true><<<grid, 256, 0, stream>>>(
-          ql, kl, pb.seq, pb.hq, pb.group, pb.window, total, c2, chunk, L.max_chunks,
-          L.row_chunks, part_m, part_s, nullptr, group_max, nullptr));
-      KVC_LAUNCH("score_merge", stream, score_merge<<<(L.rows_layer + 255) / 256, 256, 0, stream>>>(
-          pb.seq, rows_per_seq, chunk, L.max_chunks, part_m, part_s, lse2));
+      const int nqb0 = (pb.group * pb.window < MF_RCHUNK ? pb.group * pb.window : MF_RCHUNK) / 32;
+#define KVC_SCORE_MFMA(NAME, EMIT, TMAX, WQ, PM, PS, LSE, OUT)                                   \
+  KVC_LAUNCH(NAME, stream, score_mfma<EMIT, TMAX, WQ><<<grid, 256, 0, stream>>>(                  \
+      ql, kl, pb.seq, pb.hq, pb.group, pb.window, total, c2, chunk, L.max_chunks, L.row_chunks,  \
+      PM, PS, LSE, group_max, OUT))
+#define KVC_SCORE_MFMA_WQ(NAME, EMIT, TMAX, PM, PS, LSE, OUT)                     \
+  do {                                                                            \
+    if (nqb0 <= 2) { KVC_SCORE_MFMA(NAME, EMIT, TMAX, 1, PM, PS, LSE, OUT); }       \
+    else if (nqb0 <= 4) { KVC_SCORE_MFMA(NAME, EMIT, TMAX, 2, PM, PS, LSE, OUT); }  \
+    else { KVC_SCORE_MFMA(NAME, EMIT, TMAX, 4, PM, PS, LSE, OUT); }                 \
+  } while (0)
+      KVC_SCORE_MFMA_WQ("score_mfma<stats>", false, true, part_m, part_s, nullptr, nullptr);
+      KVC_LAUNCH("score_merge", stream, score_merge<<<(L.rows_layer + MERGE_ROWS - 1) / MERGE_ROWS, 256, 0, stream>>>(
+          pb.seq, rows_per_seq, chunk, part_m, part_s, lse2));
       if (task_max) {
-        KVC_LAUNCH("score_mfma<emit>", stream, score_mfma<true, true><<<grid, 256, 0, stream>>>(
-            ql, kl, pb.seq, pb.hq, pb.group, pb.window, total, c2, chunk, L.max_chunks,
-            L.row_chunks, nullptr, nullptr, lse2, group_max, part));
+        KVC_SCORE_MFMA_WQ("score_mfma<emit>", true, true, nullptr, nullptr, lse2, part);
       } else {
-        KVC_LAUNCH("score_mfma<emit>", stream, score_mfma<true, false><<<grid, 256, 0, stream>>>(
-            ql, kl, pb.seq, pb.hq, pb.group, pb.window, total, c2, chunk, L.max_chunks,
-            L.row_chunks, nullptr, nullptr, lse2, group_max, part));
+        KVC_SCORE_MFMA_WQ("score_mfma<emit>", true, false, nullptr, nullptr, lse2, part);
       }
+#undef KVC_SCORE_MFMA_WQ
+#undef KVC_SCORE_MFMA
     } else {
       const int row_blocks = (pb.window + GEN_RB - 1) / GEN_RB;
       dim3 gs(chunks, pb.hq * row_blocks, pb.batch), ge(chunks, pb.hkv, pb.batch);
@@ -542,8 +344,8 @@ kvc_status launch_score(const Problem& pb, const void* const* q, const void* con
         KVC_LAUNCH("score_stats_generic", stream, score_stats_generic<uint16_t><<<gs, 256, lds_s, stream>>>(
             ql, kl, pb.seq, pb.hq, pb.group, pb.window, pb.d, total, c2, chunk, L.max_chunks,
             part_m, part_s));
-        KVC_LAUNCH("score_merge", stream, score_merge<<<(L.rows_layer + 255) / 256, 256, 0, stream>>>(
-            pb.seq, rows_per_seq, chunk, L.max_chunks, part_m, part_s, lse2));
+        KVC_LAUNCH("score_merge", stream, score_merge<<<(L.rows_layer + MERGE_ROWS - 1) / MERGE_ROWS, 256, 0, stream>>>(
+            pb.seq, rows_per_seq, chunk, part_m, part_s, lse2));
         KVC_LAUNCH("score_emit_generic", stream, score_emit_generic<uint16_t><<<ge, 256, lds_e, stream>>>(
             ql, kl, pb.seq, pb.hq, pb.group, pb.window, pb.d, total, c2, chunk, lse2, task_max,
             group_max, part));
@@ -553,8 +355,8 @@ kvc_status launch_score(const Problem& pb, const void* const* q, const void* con
         KVC_LAUNCH("score_stats_generic", stream, score_stats_generic<float><<<gs, 256, lds_s, stream>>>(
             ql, kl, pb.seq, pb.hq, pb.group, pb.window, pb.d, total, c2, chunk, L.max_chunks,
             part_m, part_s));
-        KVC_LAUNCH("score_merge", stream, score_merge<<<(L.rows_layer + 255) / 256, 256, 0, stream>>>(
-            pb.seq, rows_per_seq, chunk, L.max_chunks, part_m, part_s, lse2));
+        KVC_LAUNCH("score_merge", stream, score_merge<<<(L.rows_layer + MERGE_ROWS - 1) / MERGE_ROWS, 256, 0, stream>>>(
+            pb.seq, rows_per_seq, chunk, part_m, part_s, lse2));
         KVC_LAUNCH("score_emit_generic", stream, score_emit_generic<float><<<ge, 256, lds_e, stream>>>(
             ql, kl, pb.seq, pb.hq, pb.group, pb.window, pb.d, total, c2, chunk, lse2, task_max,
             group_max, part));
