@@ -21,7 +21,7 @@ def hipcc() -> str:
 
 def build(verbose: bool = False) -> str:
     cmd = [hipcc(), "-O3", "-std=c++17", "--offload-arch=gfx950", "-shared", "-fPIC",
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-fno-honor-nans",
            "-I", os.path.join(ROOT, "include"), "-I", CSRC,
            "-o", LIB] + [os.path.join(CSRC, s) for s in SOURCES]
     if verbose:

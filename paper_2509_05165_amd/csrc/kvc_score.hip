@@ -257,7 +257,7 @@ __global__ void score_finish(const float* part, int row_chunks, int hkv, int tot
 
 
 constexpr int GEN_CHUNK = 256;
-constexpr int MF_CHUNK = 1024;
+constexpr int MF_CHUNK = 2048;
 constexpr int MIN_CHUNK = 256;   // workspace is sized for the smallest chunk in use
 
 struct ScoreLayout {
@@ -314,8 +314,8 @@ kvc_status launch_score(const Problem& pb, const void* const* q, const void* con
       dim3 grid(chunks, pb.hkv * L.row_chunks, pb.batch);
       const int nqb0 = (pb.group * pb.window < MF_RCHUNK ? pb.group * pb.window : MF_RCHUNK) / 32;
 #define KVC_SCORE_MFMA(NAME, EMIT, TMAX, WQ, PM, PS, LSE, OUT)                                   \
-  KVC_LAUNCH(NAME, stream, score_mfma<EMIT, TMAX, WQ><<<grid, 256, 0, stream>>>(                  \
-      ql, kl, pb.seq, pb.hq, pb.group, pb.window, total, c2, chunk, L.max_chunks, L.row_chunks,  \
+  KVC_LAUNCH(NAME, stream, score_mfma<EMIT, TMAX, WQ><<<grid, MF_THREADS, 0, stream>>>(           \
+      ql, kl, pb.seq, pb.hq, pb.group, pb.window, total, c2, chunk, L.row_chunks,                \
       PM, PS, LSE, group_max, OUT))
 #define KVC_SCORE_MFMA_WQ(NAME, EMIT, TMAX, PM, PS, LSE, OUT)                     \
   do {                                                                            \

@@ -3,10 +3,20 @@
 //
 // One workgroup (4 waves) handles one KV head x one chunk of keys x up to 256
 // query rows (8 blocks of 32 rows).  A wave owns two query blocks whose
-// fragments stay in registers; K streams through LDS in 128-key macro tiles.
+// fragments stay in registers for the whole kernel.  K streams through LDS in
+// 128-key macro tiles written by direct global->LDS loads (no staging
+// registers), one tile ahead of the MFMAs, in two buffers.  Inside a wave the
+// MFMAs of one 32-key tile are interleaved with the softmax arithmetic of the
+// previous tile (two accumulator sets), so the matrix pipe and the vector ALU
+// work at the same time.
+//
 // v_mfma_f32_32x32x16_bf16 fragment layout (wave64): operand lane l holds, for
 // row/column (l % 32), the 8 consecutive k-values 8*(l/32) .. +7; accumulator
 // register r of lane l is element (row 8*(r/4) + 4*(l/32) + r%4, column l%32).
+//
+// LDS tile layout: row (key) r at byte 256*r, its sixteen 16-byte pieces stored
+// at slot (piece ^ (r & 15)), so the fragment reads of 16 consecutive rows hit
+// 16 different slots (all banks) although rows are exactly one bank-stride apart.
 #pragma once
 
 namespace kvc {
@@ -16,70 +26,122 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int MF_D = 128;
+constexpr int MF_THREADS = 256;
 constexpr int MF_TILE = 128;                 // keys per LDS macro tile
-constexpr int MF_ROWB = MF_D * 2 + 16;       // padded LDS row: 272 bytes
 constexpr int MF_RCHUNK = 256;               // query rows per workgroup
-constexpr int MF_KBUF = MF_TILE * MF_ROWB;   // bytes per K buffer
+constexpr int MF_KBUF = MF_TILE * 256;       // bytes per K buffer
+constexpr int MF_NBUF = 2;
+constexpr int MF_DMA = MF_KBUF / 16 / MF_THREADS;   // direct loads per thread per tile (8)
 
 __device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
 __device__ __forceinline__ int acc_row(int r, int half) { return 8 * (r >> 2) + 4 * half + (r & 3); }
 
-// Eight 16-byte pieces per thread cover one 128-key x 256-byte macro tile:
-// piece i of thread t is row 16*i + t/16, bytes 16*(t%16) .. +15.
-struct KStage { uint4 a, b, c, d, e, f, g, h; };
-
-// Full tile: every row exists.  src points at this thread's piece 0 of the tile.
-__device__ __forceinline__ void stage_load_full(KStage& s, const uint16_t* src) {
-  constexpr int STEP = 16 * MF_D;   // 16 rows further
-  s.a = *reinterpret_cast<const uint4*>(src);
-  s.b = *reinterpret_cast<const uint4*>(src + STEP);
-  s.c = *reinterpret_cast<const uint4*>(src + 2 * STEP);
-  s.d = *reinterpret_cast<const uint4*>(src + 3 * STEP);
-  s.e = *reinterpret_cast<const uint4*>(src + 4 * STEP);
-  s.f = *reinterpret_cast<const uint4*>(src + 5 * STEP);
-  s.g = *reinterpret_cast<const uint4*>(src + 6 * STEP);
-  s.h = *reinterpret_cast<const uint4*>(src + 7 * STEP);
+// 16 bytes per lane straight from global memory into LDS: lane i of the wave
+// writes LDS bytes [lds_base + 16 i, +16).  lds_base must be wave-uniform.  The
+// load is tracked by vmcnt only; the caller orders it with wait_vmcnt + barrier.
+__device__ __forceinline__ void lds_dma16(const void* gptr, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr)
+               : "memory");
 }
-// Ragged tile: rows at or past `rows_left` re-read the last valid row.
-__device__ __forceinline__ uint4 ld_clamped(const uint16_t* tile, int rows_left, int i) {
-  const int row = min(16 * i + ((int)threadIdx.x >> 4), rows_left - 1);
-  return *reinterpret_cast<const uint4*>(tile + (size_t)row * MF_D + ((int)threadIdx.x & 15) * 8);
-}
-__device__ __forceinline__ void stage_load_ragged(KStage& s, const uint16_t* tile, int rows_left) {
-  s.a = ld_clamped(tile, rows_left, 0); s.b = ld_clamped(tile, rows_left, 1);
-  s.c = ld_clamped(tile, rows_left, 2); s.d = ld_clamped(tile, rows_left, 3);
-  s.e = ld_clamped(tile, rows_left, 4); s.f = ld_clamped(tile, rows_left, 5);
-  s.g = ld_clamped(tile, rows_left, 6); s.h = ld_clamped(tile, rows_left, 7);
-}
-__device__ __forceinline__ void stage_store(const KStage& s, unsigned char* dst) {
-  constexpr int STEP = 16 * MF_ROWB;
-  *reinterpret_cast<uint4*>(dst) = s.a;
-  *reinterpret_cast<uint4*>(dst + STEP) = s.b;
-  *reinterpret_cast<uint4*>(dst + 2 * STEP) = s.c;
-  *reinterpret_cast<uint4*>(dst + 3 * STEP) = s.d;
-  *reinterpret_cast<uint4*>(dst + 4 * STEP) = s.e;
-  *reinterpret_cast<uint4*>(dst + 5 * STEP) = s.f;
-  *reinterpret_cast<uint4*>(dst + 6 * STEP) = s.g;
-  *reinterpret_cast<uint4*>(dst + 7 * STEP) = s.h;
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-struct KFrag { uint4 v[8]; };
-__device__ __forceinline__ void frag_load(KFrag& f, const unsigned char* kp) {
+// Combine the two half-waves: both halves end up with op(lower, upper).
+template <bool MAX>
+__device__ __forceinline__ float cross_half(float v) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  const float a = __uint_as_float(r[0]), b = __uint_as_float(r[1]);
+  return MAX ? fmaxf(a, b) : a + b;
+}
+
+// STATS: fold one 32x32 logit tile (keys on rows) into the lane's running
+// (max, sum 2^(t - max)) of its query column.
+__device__ __forceinline__ void stats_fold(const f32x16& acc, float c2, float& mrun, float& srun) {
+  float amax = acc[0];
 #pragma unroll
-  for (int ks = 0; ks < 8; ++ks) f.v[ks] = *reinterpret_cast<const uint4*>(kp + ks * 32);
+  for (int r = 1; r < 16; ++r) amax = fmaxf(amax, acc[r]);
+  const float mn = fmaxf(mrun, amax * c2);
+  float s = srun * fast_exp2(mrun - mn);
+  const float nmn = -mn;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) s += fast_exp2(fmaf(acc[r], c2, nmn));
+  srun = s;
+  mrun = mn;
+}
+
+// The same fold for two tiles (x0, x1), cut into 16 slices so that slice i can be
+// issued right behind MFMA i of the next tile.  Slices 0-1: tile maxima; slice
+// 2: new running maxima and rescale; slices 3-15: the 32 exponentials.
+struct StatsCarry { float amax[2], nmn[2], s[2]; };
+__device__ __forceinline__ void stats_slice(int i, const f32x16& x0, const f32x16& x1, float c2,
+                                            float (&mrun)[2], float (&srun)[2], StatsCarry& c) {
+  if (i < 2) {
+    const f32x16& x = i ? x1 : x0;
+    float m = fmaxf(x[0], x[1]);
+#pragma unroll
+    for (int r = 2; r < 16; r += 2) m = fmaxf(m, fmaxf(x[r], x[r + 1]));
+    c.amax[i] = m;
+  } else if (i == 2) {
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+      const float mn = fmaxf(mrun[b], c.amax[b] * c2);
+      c.s[b] = srun[b] * fast_exp2(mrun[b] - mn);
+      c.nmn[b] = -mn;
+      mrun[b] = mn;
+    }
+  } else {
+    // elements 0..31 (tile 0 then tile 1): slices 3..8 take three, 9..15 take two
+    const int first = i <= 8 ? 3 * (i - 3) : 18 + 2 * (i - 9);
+    const int count = i <= 8 ? 3 : 2;
+#pragma unroll
+    for (int e = first; e < first + count; ++e) {
+      const int b = e >> 4, r = e & 15;
+      const float v = b ? x1[r] : x0[r];
+      c.s[b] += fast_exp2(fmaf(v, c2, c.nmn[b]));
+    }
+    if (i == 15) { srun[0] = c.s[0]; srun[1] = c.s[1]; }
+  }
+}
+
+// EMIT: reduce one 32x32 logit tile (queries on rows) over its 32 query rows:
+// max of t, or sum of 2^t, with t = logit*c2 - lse2.  Result in both half-waves.
+template <bool TASK_MAX>
+__device__ __forceinline__ float emit_fold(const f32x16& acc, float c2, const float (&nl)[16]) {
+  float v = TASK_MAX ? NEG_BIG : 0.f;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const float t = fmaf(acc[r], c2, nl[r]);
+    v = TASK_MAX ? fmaxf(v, t) : v + fast_exp2(t);
+  }
+  return cross_half<TASK_MAX>(v);
+}
+// The same for two tiles in 16 slices: slice i handles elements 2(i%8), 2(i%8)+1 of
+// tile i/8; the cross-half combine of a tile follows its last slice.
+template <bool TASK_MAX>
+__device__ __forceinline__ void emit_slice(int i, const f32x16& x0, const f32x16& x1, float c2,
+                                           const float (&nl)[2][16], float (&v)[2]) {
+  const int b = i >> 3, r = 2 * (i & 7);
+  const f32x16& x = b ? x1 : x0;
+  if ((i & 7) == 0) v[b] = TASK_MAX ? NEG_BIG : 0.f;
+  const float t0 = fmaf(x[r], c2, nl[b][r]), t1 = fmaf(x[r + 1], c2, nl[b][r + 1]);
+  if (TASK_MAX) v[b] = fmaxf(v[b], fmaxf(t0, t1));
+  else v[b] += fast_exp2(t0) + fast_exp2(t1);
+  if ((i & 7) == 7) v[b] = cross_half<TASK_MAX>(v[b]);
 }
 
 // grid: (chunks, Hkv * row_chunks, Bt), 256 threads.  WQ = waves along the query
 // rows (each owns 2 blocks of 32 rows); the other 4/WQ waves split the key tiles.
 template <bool EMIT, bool TASK_MAX, int WQ>
-__global__ __launch_bounds__(256, 2) void score_mfma(
+__global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
     const uint16_t* __restrict__ q_layer, const uint16_t* __restrict__ k_layer, SeqTable seq,
-    int hq, int group, int window, int total, float c2, int chunk_keys, int max_chunks,
-    int row_chunks, float* __restrict__ part_m, float* __restrict__ part_s,
-    const float* __restrict__ lse2, int group_max, float* __restrict__ out) {
+    int hq, int group, int window, int total, float c2, int chunk_keys, int row_chunks,
+    float* __restrict__ part_m, float* __restrict__ part_s, const float* __restrict__ lse2,
+    int group_max, float* __restrict__ out) {
   constexpr int WK = 4 / WQ;        // waves along the keys
   constexpr int NT = 4 / WK;        // 32-key tiles per wave per macro tile
-  __shared__ __attribute__((aligned(16))) unsigned char kbuf[2][MF_KBUF];
+  __shared__ __attribute__((aligned(1024))) unsigned char kbuf[MF_NBUF][MF_KBUF];
   __shared__ float red[EMIT ? 2 : 1][8][EMIT ? MF_TILE : 1];   // EMIT: (q block, key) task aggregate
   __shared__ float stat[EMIT ? 1 : 4][2][32][2];               // STATS: per wave (max, sum)
 
@@ -97,6 +159,33 @@ __global__ __launch_bounds__(256, 2) void score_mfma(
   const int wq = wave % WQ, wk = wave / WQ;
   const int col = lane & 31, half = lane >> 5;
   const uint16_t* k_chunk = k_layer + ((size_t)h * total + tok0 + key_begin) * MF_D;
+
+  const int span = key_end - key_begin;
+  const int nfull = span / MF_TILE;             // macro tiles with all 128 keys
+  const int tail = span - nfull * MF_TILE;      // keys of the ragged last tile (0 = none)
+  const int ntiles = nfull + (tail > 0);
+
+  // ---- direct global->LDS tile loads ----
+  // load j of this thread: tile row 16 j + 4 wave + lane/16, LDS slot lane%16
+  const int drow = wave * 4 + (lane >> 4);
+  const int dpiece = (lane & 15) ^ (drow & 15);          // piece of the row that lands in my slot
+  const uint32_t kbuf_lds =
+      (uint32_t)(size_t)(__attribute__((address_space(3))) unsigned char*)(&kbuf[0][0]);
+  const uint32_t dma_lds = __builtin_amdgcn_readfirstlane(kbuf_lds + wave * 1024);
+  auto issue_tile = [&](int t) {
+    const uint16_t* tile = k_chunk + (size_t)t * MF_TILE * MF_D;
+    const uint32_t dst = dma_lds + (uint32_t)(t & 1) * MF_KBUF;
+    if (t < nfull) {
+#pragma unroll
+      for (int j = 0; j < MF_DMA; ++j)
+        lds_dma16(tile + (size_t)(16 * j + drow) * MF_D + dpiece * 8, dst + j * 4096);
+    } else {   // ragged: rows past the sequence re-read the last valid row (masked later)
+#pragma unroll
+      for (int j = 0; j < MF_DMA; ++j)
+        lds_dma16(tile + (size_t)min(16 * j + drow, tail - 1) * MF_D + dpiece * 8, dst + j * 4096);
+    }
+  };
+  issue_tile(0);
 
   // ---- query fragments: registers for the whole kernel ----
   uint4 qf[2][8];
@@ -138,97 +227,130 @@ __global__ __launch_bounds__(256, 2) void score_mfma(
   const int bpg = window / 32;                                 // q blocks per query head
   const int gcount = nqb / bpg;                                // query heads in this row chunk
 
-  const int span = key_end - key_begin;
-  const int nfull = span / MF_TILE;             // macro tiles with all 128 keys
-  const int tail = span - nfull * MF_TILE;      // keys of the ragged last tile (0 = none)
-  const int ntiles = nfull + (tail > 0);
+  // fragment addresses inside a buffer: key tile 0, k-step ks
+  int foff[8];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) foff[ks] = col * 256 + (((2 * ks + half) ^ (col & 15)) << 4);
 
-  // this thread's piece 0 inside a macro tile, in global memory and in LDS
-  const uint16_t* gsrc = k_chunk + (size_t)(threadIdx.x >> 4) * MF_D + (threadIdx.x & 15) * 8;
-  const int lds_piece = (threadIdx.x >> 4) * MF_ROWB + (threadIdx.x & 15) * 16;
-  // this lane's fragment base inside a macro tile (key tile 0, k-step 0)
-  const int lds_frag = col * MF_ROWB + half * 16;
+  // Two accumulator sets.  STATS keeps one tile "pending" across macro tiles; a
+  // pending set full of -inf folds to exactly nothing (its maximum never wins and
+  // every 2^(-inf) is 0), so the first phase needs no special case.
+  f32x16 acc[2][2];
+  const float ninf = -__builtin_inff();
+#pragma unroll
+  for (int r = 0; r < 16; ++r) { acc[1][0][r] = ninf; acc[1][1][r] = ninf; }
 
-  KStage st;
-  if (nfull > 0) stage_load_full(st, gsrc);
-  else stage_load_ragged(st, k_chunk, tail);
-  stage_store(st, kbuf[0] + lds_piece);
+  auto mfma_tile = [&](f32x16 (&a)[2], const uint4 (&kf)[8]) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { a[0][r] = 0.f; a[1][r] = 0.f; }
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      const bf16x8 kfr = as_bf16x8(kf[ks]);
+      if (EMIT) {   // rows = queries, columns = keys
+        a[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(qf[0][ks]), kfr, a[0], 0, 0, 0);
+        a[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(qf[1][ks]), kfr, a[1], 0, 0, 0);
+      } else {      // rows = keys, columns = queries
+        a[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr, as_bf16x8(qf[0][ks]), a[0], 0, 0, 0);
+        a[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr, as_bf16x8(qf[1][ks]), a[1], 0, 0, 0);
+      }
+    }
+  };
+  auto load_frags = [&](uint4 (&kf)[8], const unsigned char* kb, int kt) {
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks)
+      kf[ks] = *reinterpret_cast<const uint4*>(kb + kt * 8192 + foff[ks]);
+  };
+  auto emit_store = [&](const f32x16 (&a)[2], int cur, int kt) {
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      const float v = emit_fold<TASK_MAX>(a[qb], c2, nl[qb]);
+      const int blk = wq * 2 + qb;
+      if (half == 0 && blk < nqb) red[cur][blk][kt * 32 + col] = v;
+    }
+  };
+
+  // tile 0 must have landed
+  wait_vmcnt<0>();
   __syncthreads();
 
   for (int it = 0; it < ntiles; ++it) {
     const int cur = it & 1;
     const int key0 = key_begin + it * MF_TILE;
-    const bool more = it + 1 < ntiles;
-    if (more) {
-      const uint16_t* nxt = k_chunk + (size_t)(it + 1) * MF_TILE * MF_D;
-      if (it + 1 < nfull) stage_load_full(st, gsrc + (size_t)(it + 1) * MF_TILE * MF_D);
-      else stage_load_ragged(st, nxt, tail);
-    }
-
+    if (it + 1 < ntiles) issue_tile(it + 1);   // its buffer was last read in iteration it-1
+    const unsigned char* kb = kbuf[cur];
     const int keys_here = it < nfull ? MF_TILE : tail;
-    const unsigned char* kb = kbuf[cur] + lds_frag;
-    KFrag kf;
-    frag_load(kf, kb + (wk * 32) * MF_ROWB);
+
+    if (it < nfull && (NT % 2 == 0)) {
+      // ---- steady state: full tile, software-pipelined phases ----
+      // Phase j: the 16 MFMAs of key tile j go to accumulator set j&1; behind MFMA i
+      // comes slice i of the vector work on the other set (the previous tile) and,
+      // after both MFMAs of a k-step, the fragment of that k-step for the next tile.
+      uint4 kf[8];
+      load_frags(kf, kb, wk);
 #pragma unroll
-    for (int j = 0; j < NT; ++j) {
-      const int kt = wk + j * WK;
-      if (kt * 32 >= keys_here) break;          // wave-uniform; only in the ragged tile
-      f32x16 acc0, acc1;
+      for (int j = 0; j < NT; ++j) {
+        const int kt = wk + j * WK;
+        const int p = j & 1;
+        const bool overlap = !EMIT || j > 0;     // EMIT starts every macro tile with no pending tile
+        StatsCarry carry;
+        float ev[2];
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int r = 0; r < 16; ++r) { acc0[r] = 0.f; acc1[r] = 0.f; }
+        for (int i = 0; i < 16; ++i) {
+          const int ks = i >> 1, qb = i & 1;
+          const bf16x8 kfr = as_bf16x8(kf[ks]);
+          const f32x16 cin = ks == 0 ? zero : acc[p][qb];
+          if (EMIT)   // rows = queries, columns = keys
+            acc[p][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(qf[qb][ks]), kfr, cin, 0, 0, 0);
+          else        // rows = keys, columns = queries
+            acc[p][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr, as_bf16x8(qf[qb][ks]), cin, 0, 0, 0);
+          if (qb == 1 && j + 1 < NT)
+            kf[ks] = *reinterpret_cast<const uint4*>(kb + (kt + WK) * 8192 + foff[ks]);
+          if (overlap) {
+            if (!EMIT) stats_slice(i, acc[p ^ 1][0], acc[p ^ 1][1], c2, mrun, srun, carry);
+            else emit_slice<TASK_MAX>(i, acc[p ^ 1][0], acc[p ^ 1][1], c2, nl, ev);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        if (EMIT && overlap) {
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-        const bf16x8 kfr = as_bf16x8(kf.v[ks]);
-        if (EMIT) {   // rows = queries, columns = keys
-          acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(qf[0][ks]), kfr, acc0, 0, 0, 0);
-          acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(qf[1][ks]), kfr, acc1, 0, 0, 0);
-        } else {      // rows = keys, columns = queries
-          acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr, as_bf16x8(qf[0][ks]), acc0, 0, 0, 0);
-          acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr, as_bf16x8(qf[1][ks]), acc1, 0, 0, 0);
+          for (int qb = 0; qb < 2; ++qb) {
+            const int blk = wq * 2 + qb;
+            if (half == 0 && blk < nqb) red[cur][blk][(kt - WK) * 32 + col] = ev[qb];
+          }
         }
       }
-      // fragments of the wave's next key tile: issued while the MFMAs drain
-      if (j + 1 < NT) frag_load(kf, kb + ((kt + WK) * 32) * MF_ROWB);
-
-      if (!EMIT) {
-        if (kt * 32 + 32 > keys_here) {      // ragged: keys past the sequence drop out
+      if (EMIT) emit_store(acc[(NT - 1) & 1], cur, wk + (NT - 1) * WK);
+    } else {
+      // ---- ragged tile (always the last) or NT == 1: one key tile at a time ----
+      if (!EMIT && (NT % 2 == 0)) {   // flush the pending tile first
+        stats_fold(acc[1][0], c2, mrun[0], srun[0]);
+        stats_fold(acc[1][1], c2, mrun[1], srun[1]);
 #pragma unroll
-          for (int r = 0; r < 16; ++r)
-            if (kt * 32 + acc_row(r, half) >= keys_here) { acc0[r] = NEG_BIG; acc1[r] = NEG_BIG; }
-        }
+        for (int r = 0; r < 16; ++r) { acc[1][0][r] = ninf; acc[1][1][r] = ninf; }
+      }
+      for (int j = 0; j < NT; ++j) {
+        const int kt = wk + j * WK;
+        if (kt * 32 >= keys_here) break;          // wave-uniform
+        uint4 kf[8];
+        load_frags(kf, kb, kt);
+        mfma_tile(acc[0], kf);
+        if (!EMIT) {
+          if (kt * 32 + 32 > keys_here) {      // keys past the sequence drop out
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
-          const f32x16& acc = qb ? acc1 : acc0;
-          float amax = acc[0];
-#pragma unroll
-          for (int r = 1; r < 16; ++r) amax = fmaxf(amax, acc[r]);
-          const float mn = fmaxf(mrun[qb], amax * c2);
-          float s = srun[qb] * fast_exp2(mrun[qb] - mn);
-          const float nmn = -mn;
-#pragma unroll
-          for (int r = 0; r < 16; ++r) s += fast_exp2(fmaf(acc[r], c2, nmn));
-          srun[qb] = s;
-          mrun[qb] = mn;
-        }
-      } else {
-#pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
-          const f32x16& acc = qb ? acc1 : acc0;
-          float v = TASK_MAX ? NEG_BIG : 0.f;
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const float t = fmaf(acc[r], c2, nl[qb][r]);
-            v = TASK_MAX ? fmaxf(v, t) : v + fast_exp2(t);
+            for (int r = 0; r < 16; ++r)
+              if (kt * 32 + acc_row(r, half) >= keys_here) { acc[0][0][r] = NEG_BIG; acc[0][1][r] = NEG_BIG; }
           }
-          const float o = __shfl_xor(v, 32);
-          v = TASK_MAX ? fmaxf(v, o) : v + o;
-          const int blk = wq * 2 + qb;
-          if (half == 0 && blk < nqb) red[cur][blk][kt * 32 + col] = v;
+          stats_fold(acc[0][0], c2, mrun[0], srun[0]);
+          stats_fold(acc[0][1], c2, mrun[1], srun[1]);
+        } else {
+          emit_store(acc[0], cur, kt);
         }
       }
     }
 
-    if (more) stage_store(st, kbuf[cur ^ 1] + lds_piece);
+    // tile it+1 must have landed before anyone reads it
+    wait_vmcnt<0>();
     __syncthreads();
 
     if (EMIT) {
@@ -250,6 +372,10 @@ __global__ __launch_bounds__(256, 2) void score_mfma(
   }
 
   if (!EMIT) {
+    if (NT % 2 == 0) {   // the tile still pending
+      stats_fold(acc[1][0], c2, mrun[0], srun[0]);
+      stats_fold(acc[1][1], c2, mrun[1], srun[1]);
+    }
     // lanes l and l+32 hold the same query over different keys
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
