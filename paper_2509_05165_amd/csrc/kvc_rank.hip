@@ -15,12 +15,20 @@ namespace {
 
 constexpr int RK_THREADS = 1024;
 constexpr int RK_WAVES = RK_THREADS / 64;
-constexpr int RK_ITEMS = 4;
+constexpr int RK_ITEMS = 8;
 constexpr int RK_TILE = RK_THREADS * RK_ITEMS;
 constexpr int RK_BINS = 256;
 
 __device__ __forceinline__ uint32_t desc_key(float f) { return ~float_to_ordered(f); }
 __device__ __forceinline__ float desc_key_to_float(uint32_t k) { return ordered_to_float(~k); }
+
+// Workgroup barrier that orders LDS traffic only: global stores still in flight
+// (the scatter of the previous tile) are not waited for.
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
 
 // lanes (among `valid`) whose 8-bit digit equals mine
 __device__ __forceinline__ uint64_t match_digit(uint32_t digit, uint64_t valid) {
@@ -39,16 +47,172 @@ __device__ __forceinline__ int lanes_below(uint64_t mask) {
                                    __builtin_amdgcn_mbcnt_lo(uint32_t(mask), 0));
 }
 
-// grid: (layers * hkv, batch); block: RK_THREADS
+struct RankShared {
+  uint32_t hist[4][RK_BINS];
+  uint32_t bucket[RK_BINS];            // next free global slot of each digit
+  uint32_t wave_cnt[RK_WAVES][RK_BINS];
+  uint32_t tstart[RK_BINS];            // first tile-local slot of each digit
+  uint32_t gbase[RK_BINS];             // global slot of an item = gbase[digit] + tile-local slot
+  uint32_t wave_tot[4];
+  uint32_t stage_k[RK_TILE];           // the tile in digit order, so that the
+  int32_t stage_v[RK_TILE];            // global writes run over consecutive slots
+};
+
+// One stable counting pass on digit PASS of a segment of n items.  PASS 0 reads
+// the scores themselves (key = inverted ordered image, value = position), the
+// last pass writes scores and positions; the others move (key, value) pairs.
+// Tiles are processed in order; item (wave w, slot e, lane l) of a tile is
+// element base + w*64*ITEMS + e*64 + l, which is also its order inside the tile.
+template <int PASS>
+__device__ __forceinline__ void radix_pass(RankShared& sh, int n, const float* __restrict__ src_f,
+                                           const uint32_t* __restrict__ src_k,
+                                           const int32_t* __restrict__ src_i,
+                                           uint32_t* __restrict__ dst_k,
+                                           int32_t* __restrict__ dst_i,
+                                           float* __restrict__ dst_f) {
+  constexpr int shift = PASS * 8;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  // exclusive scan of hist[PASS] -> bucket (first 256 threads = 4 waves)
+  if (tid < RK_BINS) {
+    const uint32_t c = sh.hist[PASS][tid];
+    uint32_t incl = c;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const uint32_t o = __shfl_up(incl, off);
+      if (lane >= off) incl += o;
+    }
+    if (lane == 63) sh.wave_tot[wave] = incl;
+    sh.bucket[tid] = incl - c;   // exclusive within the wave
+  }
+  __syncthreads();
+  if (tid < RK_BINS) {
+    uint32_t add = 0;
+    for (int w = 0; w < wave; ++w) add += sh.wave_tot[w];
+    sh.bucket[tid] += add;
+  }
+  __syncthreads();
+
+  uint32_t key[RK_ITEMS], nkey[RK_ITEMS];
+  int32_t val[RK_ITEMS], nval[RK_ITEMS];
+  const int woff = wave * 64 * RK_ITEMS + lane;
+  // loads of one tile; positions past the segment re-read its last element
+#define KVC_RANK_LOAD_TILE(BASE, K, V)                         \
+  _Pragma("unroll") for (int e = 0; e < RK_ITEMS; ++e) {       \
+    const int pos = (BASE) + woff + e * 64;                    \
+    const int cpos = pos < n ? pos : n - 1;                    \
+    if (PASS == 0) { K[e] = __float_as_uint(src_f[cpos]); V[e] = cpos; } \
+    else { K[e] = src_k[cpos]; V[e] = src_i[cpos]; }           \
+  }
+  KVC_RANK_LOAD_TILE(0, key, val)
+
+  for (int base = 0; base < n; base += RK_TILE) {
+    // next tile's loads fly while this one is ranked and scattered
+    const int nbase = base + RK_TILE < n ? base + RK_TILE : base;
+    KVC_RANK_LOAD_TILE(nbase, nkey, nval)
+    if (PASS == 0) {
+#pragma unroll
+      for (int e = 0; e < RK_ITEMS; ++e) key[e] = desc_key(__uint_as_float(key[e]));
+    }
+
+    uint32_t rank[RK_ITEMS];
+    const int wbase = base + woff;
+    // zero this wave's counters (only this wave touches them until the barrier)
+#pragma unroll
+    for (int i = 0; i < RK_BINS / 64; ++i) sh.wave_cnt[wave][i * 64 + lane] = 0;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int e = 0; e < RK_ITEMS; ++e) {
+      const bool valid = wbase + e * 64 < n;
+      const uint64_t vmask = __ballot(valid);
+      const uint32_t digit = (key[e] >> shift) & 255u;
+      const uint64_t mask = match_digit(digit, vmask);
+      const int below = lanes_below(mask);
+      uint32_t prev = 0;
+      if (valid) prev = sh.wave_cnt[wave][digit];
+      rank[e] = prev + below;
+      __builtin_amdgcn_wave_barrier();
+      if (valid && below == 0) sh.wave_cnt[wave][digit] = prev + (uint32_t)__popcll(mask);
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+    }
+    lds_barrier();
+    // wave 0, lane l owns digits 4l..4l+3: per-wave counts -> prefixes inside the
+    // digit, digit totals -> tile-local start slots and the global base
+    if (wave == 0) {
+      uint32_t run[4] = {0, 0, 0, 0};
+#pragma unroll
+      for (int w = 0; w < RK_WAVES; ++w) {
+        uint4* cell = reinterpret_cast<uint4*>(&sh.wave_cnt[w][4 * lane]);
+        const uint4 c = *cell;
+        *cell = make_uint4(run[0], run[1], run[2], run[3]);
+        run[0] += c.x; run[1] += c.y; run[2] += c.z; run[3] += c.w;
+      }
+      const uint32_t mine = run[0] + run[1] + run[2] + run[3];
+      uint32_t incl = mine;
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t o = __shfl_up(incl, off);
+        if (lane >= off) incl += o;
+      }
+      uint32_t start = incl - mine;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int d = 4 * lane + j;
+        const uint32_t g = sh.bucket[d];
+        sh.tstart[d] = start;
+        sh.gbase[d] = g - start;
+        sh.bucket[d] = g + run[j];
+        start += run[j];
+      }
+    }
+    lds_barrier();
+    // every item goes to its tile-local slot
+#pragma unroll
+    for (int e = 0; e < RK_ITEMS; ++e) {
+      if (wbase + e * 64 < n) {
+        const uint32_t digit = (key[e] >> shift) & 255u;
+        const uint32_t slot = sh.tstart[digit] + sh.wave_cnt[wave][digit] + rank[e];
+        sh.stage_k[slot] = key[e];
+        sh.stage_v[slot] = val[e];
+      }
+    }
+    lds_barrier();
+    // consecutive threads write consecutive global slots within a digit run
+    const int tile_n = min(RK_TILE, n - base);
+#pragma unroll
+    for (int e = 0; e < RK_ITEMS; ++e) {
+      const int slot = e * RK_THREADS + tid;
+      if (slot < tile_n) {
+        const uint32_t k = sh.stage_k[slot];
+        const int32_t v = sh.stage_v[slot];
+        const uint32_t dst = sh.gbase[(k >> shift) & 255u] + (uint32_t)slot;
+        if (PASS == 3) {
+          dst_f[dst] = desc_key_to_float(k);
+          dst_i[dst] = v;
+        } else {
+          dst_k[dst] = k;
+          dst_i[dst] = v;
+        }
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < RK_ITEMS; ++e) { key[e] = nkey[e]; val[e] = nval[e]; }
+  }
+#undef KVC_RANK_LOAD_TILE
+  // the next pass reads what this one scattered: full fence + barrier
+  __threadfence_block();
+  __syncthreads();
+}
+
+// grid: (layers * hkv, batch); block: RK_THREADS.  One workgroup sorts one
+// segment: 4 stable passes of 8 bits, ping-pong between the workspace pair
+// (tmp_keys, tmp_idx) and the output arrays.
 __global__ __launch_bounds__(RK_THREADS) void head_rank_kernel(
     const float* __restrict__ S, SeqTable seq, int total, int32_t* __restrict__ idx_out,
     float* __restrict__ sorted_out, uint32_t* __restrict__ tmp_keys,
     int32_t* __restrict__ tmp_idx) {
-  __shared__ uint32_t hist[4][RK_BINS];
-  __shared__ uint32_t bucket[RK_BINS];            // next free slot of each digit
-  __shared__ uint32_t wave_cnt[RK_WAVES][RK_BINS];
-  __shared__ uint32_t wave_tot[4];
-
+  __shared__ RankShared sh;
   const int b = blockIdx.y;
   const int n = seq.cu[b + 1] - seq.cu[b];
   if (n == 0) return;
@@ -58,117 +222,24 @@ __global__ __launch_bounds__(RK_THREADS) void head_rank_kernel(
   int32_t* a_idx = tmp_idx + seg;
   uint32_t* b_keys = reinterpret_cast<uint32_t*>(sorted_out) + seg;
   int32_t* b_idx = idx_out + seg;
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x;
 
   // ---- histograms of all four digits in one sweep ----
-  for (int i = tid; i < 4 * RK_BINS; i += RK_THREADS) (&hist[0][0])[i] = 0;
+  for (int i = tid; i < 4 * RK_BINS; i += RK_THREADS) (&sh.hist[0][0])[i] = 0;
   __syncthreads();
   for (int i = tid; i < n; i += RK_THREADS) {
     const uint32_t key = desc_key(src_f[i]);
-    atomicAdd(&hist[0][key & 255u], 1u);
-    atomicAdd(&hist[1][(key >> 8) & 255u], 1u);
-    atomicAdd(&hist[2][(key >> 16) & 255u], 1u);
-    atomicAdd(&hist[3][key >> 24], 1u);
+    atomicAdd(&sh.hist[0][key & 255u], 1u);
+    atomicAdd(&sh.hist[1][(key >> 8) & 255u], 1u);
+    atomicAdd(&sh.hist[2][(key >> 16) & 255u], 1u);
+    atomicAdd(&sh.hist[3][key >> 24], 1u);
   }
   __syncthreads();
 
-  for (int pass = 0; pass < 4; ++pass) {
-    const int shift = pass * 8;
-    // exclusive scan of hist[pass] -> bucket (first 256 threads = 4 waves)
-    if (tid < RK_BINS) {
-      const uint32_t c = hist[pass][tid];
-      uint32_t incl = c;
-#pragma unroll
-      for (int off = 1; off < 64; off <<= 1) {
-        const uint32_t o = __shfl_up(incl, off);
-        if (lane >= off) incl += o;
-      }
-      if (lane == 63) wave_tot[wave] = incl;
-      bucket[tid] = incl - c;   // exclusive within the wave
-    }
-    __syncthreads();
-    if (tid < RK_BINS) {
-      uint32_t add = 0;
-      for (int w = 0; w < wave; ++w) add += wave_tot[w];
-      bucket[tid] += add;
-    }
-    __syncthreads();
-
-    const uint32_t* src_k = (pass == 2) ? b_keys : a_keys;   // pass 0 reads S itself
-    const int32_t* src_i = (pass == 2) ? b_idx : a_idx;
-    uint32_t* dst_k = (pass & 1) ? b_keys : a_keys;
-    int32_t* dst_i = (pass & 1) ? b_idx : a_idx;
-
-    for (int base = 0; base < n; base += RK_TILE) {
-      uint32_t key[RK_ITEMS];
-      int32_t val[RK_ITEMS];
-      uint32_t rank[RK_ITEMS];
-      const int wbase = base + wave * 64 * RK_ITEMS;
-#pragma unroll
-      for (int e = 0; e < RK_ITEMS; ++e) {
-        const int pos = wbase + e * 64 + lane;
-        key[e] = 0xffffffffu;
-        val[e] = 0;
-        if (pos < n) {
-          if (pass == 0) { key[e] = desc_key(src_f[pos]); val[e] = pos; }
-          else { key[e] = src_k[pos]; val[e] = src_i[pos]; }
-        }
-      }
-      // zero this wave's counters
-#pragma unroll
-      for (int i = 0; i < RK_BINS / 64; ++i) wave_cnt[wave][i * 64 + lane] = 0;
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-#pragma unroll
-      for (int e = 0; e < RK_ITEMS; ++e) {
-        const int pos = wbase + e * 64 + lane;
-        const bool valid = pos < n;
-        const uint64_t vmask = __ballot(valid);
-        const uint32_t digit = (key[e] >> shift) & 255u;
-        const uint64_t mask = match_digit(digit, vmask);
-        const int below = lanes_below(mask);
-        uint32_t prev = 0;
-        if (valid) prev = wave_cnt[wave][digit];
-        rank[e] = prev + below;
-        __builtin_amdgcn_wave_barrier();
-        if (valid && below == 0) wave_cnt[wave][digit] = prev + (uint32_t)__popcll(mask);
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-      }
-      __syncthreads();
-      // per digit: turn per-wave counts into absolute start slots
-      if (tid < RK_BINS) {
-        uint32_t run = bucket[tid];
-#pragma unroll
-        for (int w = 0; w < RK_WAVES; ++w) {
-          const uint32_t c = wave_cnt[w][tid];
-          wave_cnt[w][tid] = run;
-          run += c;
-        }
-        bucket[tid] = run;
-      }
-      __syncthreads();
-#pragma unroll
-      for (int e = 0; e < RK_ITEMS; ++e) {
-        const int pos = wbase + e * 64 + lane;
-        if (pos < n) {
-          const uint32_t digit = (key[e] >> shift) & 255u;
-          const uint32_t dst = wave_cnt[wave][digit] + rank[e];
-          if (pass == 3) {
-            sorted_out[seg + dst] = desc_key_to_float(key[e]);
-            b_idx[dst] = val[e];
-          } else {
-            dst_k[dst] = key[e];
-            dst_i[dst] = val[e];
-          }
-        }
-      }
-      __syncthreads();
-    }
-    // make this pass's global writes visible to the whole workgroup
-    __threadfence_block();
-    __syncthreads();
-  }
+  radix_pass<0>(sh, n, src_f, nullptr, nullptr, a_keys, a_idx, nullptr);
+  radix_pass<1>(sh, n, nullptr, a_keys, a_idx, b_keys, b_idx, nullptr);
+  radix_pass<2>(sh, n, nullptr, b_keys, b_idx, a_keys, a_idx, nullptr);
+  radix_pass<3>(sh, n, nullptr, a_keys, a_idx, nullptr, b_idx, sorted_out + seg);
 }
 
 // grid: (token blocks, layers)
