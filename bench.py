@@ -96,6 +96,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=3)
     ap.add_argument("--workers", type=int, default=min(16, os.cpu_count() or 1))
+    ap.add_argument("--copy-probe", type=int, default=0, metavar="MB",
+                    help="only run the library's plain copy kernel on MB MiB (counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU; this build uses no second GPU (run with --gpus 1)",
@@ -108,6 +110,18 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.copy_probe:
+        nbytes = args.copy_probe << 20
+        src = torch.ones(nbytes, dtype=torch.uint8, device="cuda")
+        dst = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+        for _ in range(3):
+            kv.kvc_copy_probe(dst.data_ptr(), src.data_ptr(), nbytes,
+                              torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        assert bool((dst == 1).all())
+        print(json.dumps({"copy_probe_bytes_read": nbytes, "copy_probe_bytes_written": nbytes,
+                          "launches": 3}))
+        return
     over = {}
     if args.n:
         over["n"] = args.n

@@ -208,6 +208,12 @@ typedef struct kvc_profile_entry {
 void kvc_profile_enable(int on);
 int kvc_profile_collect(kvc_profile_entry* out, int capacity);
 
+/* Measurement aid: one plain device-to-device streaming copy of `bytes` bytes
+ * (a positive multiple of 16; dst and src are device buffers that must not
+ * overlap).  Its known traffic (bytes read + bytes written) is what hardware
+ * byte counters are scaled against. */
+kvc_status kvc_copy_probe(void* dst, const void* src, size_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

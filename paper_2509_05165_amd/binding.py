@@ -202,3 +202,10 @@ def kvc_profile_collect(capacity: int = 64):
     if n < 0:
         raise KvcError(4, "kvc_profile_collect", "HIP event query failed")
     return {buf[i].name.decode(): (buf[i].launches, buf[i].total_ms) for i in range(min(n, capacity))}
+
+
+def kvc_copy_probe(dst, src, nbytes: int, stream=0) -> None:
+    fn = lib().kvc_copy_probe
+    fn.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    fn.restype = C.c_int
+    _check(fn(_vp(dst), _vp(src), nbytes, _vp(stream)), "kvc_copy_probe")

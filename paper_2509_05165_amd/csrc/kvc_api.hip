@@ -326,6 +326,14 @@ kvc_status kvc_gather(const kvc_params* params, const void* const* k, const void
                        static_cast<hipStream_t>(stream));
 }
 
+kvc_status kvc_copy_probe(void* dst, const void* src, size_t bytes, void* stream) {
+  if (!dst || !src || bytes == 0 || bytes % 16 != 0) {
+    set_error("copy probe needs non-null buffers and a positive multiple of 16 bytes");
+    return KVC_ERR_INVALID_ARG;
+  }
+  return launch_copy_probe(dst, src, bytes, static_cast<hipStream_t>(stream));
+}
+
 kvc_status kvc_compress(const kvc_params* params, const kvc_inputs* in, const kvc_outputs* out,
                         void* workspace, size_t workspace_bytes, void* stream) {
   if (!in || !out) { set_error("inputs or outputs is NULL"); return KVC_ERR_INVALID_ARG; }

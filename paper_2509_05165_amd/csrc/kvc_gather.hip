@@ -94,7 +94,23 @@ __global__ __launch_bounds__(GA_THREADS) void gather_kernel(
   }
 }
 
+// Plain streaming copy (16 bytes per lane), used only to calibrate hardware
+// counters against a known byte count.
+__global__ __launch_bounds__(256) void copy_probe_kernel(const uint4* __restrict__ src,
+                                                         uint4* __restrict__ dst, size_t n16) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16;
+       i += (size_t)gridDim.x * blockDim.x)
+    dst[i] = src[i];
+}
+
 }  // namespace
+
+kvc_status launch_copy_probe(void* dst, const void* src, size_t bytes, hipStream_t stream) {
+  const size_t n16 = bytes / 16;
+  KVC_LAUNCH("copy_probe_kernel", stream, copy_probe_kernel<<<8192, 256, 0, stream>>>(
+      static_cast<const uint4*>(src), static_cast<uint4*>(dst), n16));
+  return KVC_OK;
+}
 
 kvc_status launch_gather(const Problem& pb, const void* const* k, const void* const* v,
                          const int32_t* idx, const int32_t* lengths, const int64_t* offsets,

@@ -74,6 +74,8 @@ kvc_status launch_gather(const Problem& pb, const void* const* k, const void* co
                          const int32_t* idx, const int32_t* lengths, const int64_t* offsets,
                          int64_t total_budget, void* k_out, void* v_out, hipStream_t stream);
 
+kvc_status launch_copy_probe(void* dst, const void* src, size_t bytes, hipStream_t stream);
+
 // ---------------------------------------------------------------------------
 // Device helpers
 // ---------------------------------------------------------------------------

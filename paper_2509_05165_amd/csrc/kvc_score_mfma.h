@@ -74,7 +74,7 @@ __device__ __forceinline__ void stats_fold(const f32x16& acc, float c2, float& m
 // The same fold for two tiles (x0, x1), cut into 16 slices so that slice i can be
 // issued right behind MFMA i of the next tile.  Slices 0-1: tile maxima; slice
 // 2: new running maxima and rescale; slices 3-15: the 32 exponentials.
-struct StatsCarry { float amax[2], nmn[2], s[2]; };
+struct StatsCarry { float amax[2], nmn[2], s[2], e[3]; int eb[3]; };
 __device__ __forceinline__ void stats_slice(int i, const f32x16& x0, const f32x16& x1, float c2,
                                             float (&mrun)[2], float (&srun)[2], StatsCarry& c) {
   if (i < 2) {
@@ -92,16 +92,29 @@ __device__ __forceinline__ void stats_slice(int i, const f32x16& x0, const f32x1
       mrun[b] = mn;
     }
   } else {
-    // elements 0..31 (tile 0 then tile 1): slices 3..8 take three, 9..15 take two
+    // elements 0..31 (tile 0 then tile 1): slices 3..8 take three, 9..15 take two.
+    // The exponentials of a slice are summed one slice later, so the adds never
+    // wait for a transcendental that has just been issued.
     const int first = i <= 8 ? 3 * (i - 3) : 18 + 2 * (i - 9);
     const int count = i <= 8 ? 3 : 2;
+    const int pfirst = i == 3 ? 0 : (i - 1 <= 8 ? 3 * (i - 4) : 18 + 2 * (i - 10));
+    const int pcount = i == 3 ? 0 : (i - 1 <= 8 ? 3 : 2);
+    float fresh[3];
 #pragma unroll
-    for (int e = first; e < first + count; ++e) {
-      const int b = e >> 4, r = e & 15;
-      const float v = b ? x1[r] : x0[r];
-      c.s[b] += fast_exp2(fmaf(v, c2, c.nmn[b]));
+    for (int j = 0; j < count; ++j) {
+      const int e = first + j, b = e >> 4, r = e & 15;
+      fresh[j] = fast_exp2(fmaf(b ? x1[r] : x0[r], c2, c.nmn[b]));
     }
-    if (i == 15) { srun[0] = c.s[0]; srun[1] = c.s[1]; }
+#pragma unroll
+    for (int j = 0; j < pcount; ++j) c.s[(pfirst + j) >> 4] += c.e[j];
+#pragma unroll
+    for (int j = 0; j < count; ++j) c.e[j] = fresh[j];
+    if (i == 15) {
+#pragma unroll
+      for (int j = 0; j < count; ++j) c.s[(first + j) >> 4] += c.e[j];
+      srun[0] = c.s[0];
+      srun[1] = c.s[1];
+    }
   }
 }
 
@@ -131,8 +144,24 @@ __device__ __forceinline__ void emit_slice(int i, const f32x16& x0, const f32x16
   if ((i & 7) == 7) v[b] = cross_half<TASK_MAX>(v[b]);
 }
 
+// 16 bytes per lane from (scalar base + per-lane byte offset) into LDS.
+__device__ __forceinline__ void lds_dma16_s(const void* sbase, uint32_t voff, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(sbase)
+               : "memory");
+}
+
 // grid: (chunks, Hkv * row_chunks, Bt), 256 threads.  WQ = waves along the query
 // rows (each owns 2 blocks of 32 rows); the other 4/WQ waves split the key tiles.
+//
+// Schedule of one workgroup over its macro tiles (two K buffers, tile t in
+// buffer t&1), for an even number NT of 32-key tiles per wave:
+//   phase j of tile t = 16 MFMAs of key tile j into accumulator set j&1, each
+//   followed by one slice of the vector work on the other set (the previous
+//   key tile, possibly of tile t-1) and by the fragment reads for the next phase;
+//   before the last phase of tile t all fragments of tile t are in registers, so
+//   the workgroup waits for tile t+1, meets at a barrier, starts the load of
+//   tile t+2 into the buffer of tile t and (EMIT) writes out tile t-1; the last
+//   phase already prefetches the first fragments of tile t+1.
 template <bool EMIT, bool TASK_MAX, int WQ>
 __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
     const uint16_t* __restrict__ q_layer, const uint16_t* __restrict__ k_layer, SeqTable seq,
@@ -141,8 +170,9 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
     int group_max, float* __restrict__ out) {
   constexpr int WK = 4 / WQ;        // waves along the keys
   constexpr int NT = 4 / WK;        // 32-key tiles per wave per macro tile
+  constexpr bool PIPE = NT % 2 == 0;
   __shared__ __attribute__((aligned(1024))) unsigned char kbuf[MF_NBUF][MF_KBUF];
-  __shared__ float red[EMIT ? 2 : 1][8][EMIT ? MF_TILE : 1];   // EMIT: (q block, key) task aggregate
+  __shared__ float red[EMIT ? 3 : 1][8][EMIT ? MF_TILE : 1];   // EMIT: per (q block | wave, key)
   __shared__ float stat[EMIT ? 1 : 4][2][32][2];               // STATS: per wave (max, sum)
 
   const int b = blockIdx.z;
@@ -172,20 +202,29 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
   const uint32_t kbuf_lds =
       (uint32_t)(size_t)(__attribute__((address_space(3))) unsigned char*)(&kbuf[0][0]);
   const uint32_t dma_lds = __builtin_amdgcn_readfirstlane(kbuf_lds + wave * 1024);
+  const uint32_t dvoff = (uint32_t)(drow * MF_D + dpiece * 8) * 2u;   // byte offset of load 0
   auto issue_tile = [&](int t) {
-    const uint16_t* tile = k_chunk + (size_t)t * MF_TILE * MF_D;
+    // scalar tile base; load j adds 16 rows (4096 bytes) to it
+    const uint64_t addr = reinterpret_cast<uint64_t>(k_chunk) + (uint64_t)t * MF_KBUF;
+    // readfirstlane returns a signed int: widen through uint32_t, or a low half
+    // with bit 31 set would sign-extend into the high half
+    const uint64_t tile =
+        ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(addr >> 32)) << 32) |
+        (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)addr);
     const uint32_t dst = dma_lds + (uint32_t)(t & 1) * MF_KBUF;
     if (t < nfull) {
 #pragma unroll
       for (int j = 0; j < MF_DMA; ++j)
-        lds_dma16(tile + (size_t)(16 * j + drow) * MF_D + dpiece * 8, dst + j * 4096);
+        lds_dma16_s(reinterpret_cast<const void*>(tile + j * 4096), dvoff, dst + j * 4096);
     } else {   // ragged: rows past the sequence re-read the last valid row (masked later)
 #pragma unroll
       for (int j = 0; j < MF_DMA; ++j)
-        lds_dma16(tile + (size_t)min(16 * j + drow, tail - 1) * MF_D + dpiece * 8, dst + j * 4096);
+        lds_dma16_s(reinterpret_cast<const void*>(tile),
+                    (uint32_t)(min(16 * j + drow, tail - 1) * MF_D + dpiece * 8) * 2u, dst + j * 4096);
     }
   };
   issue_tile(0);
+  if (ntiles > 1) issue_tile(1);
 
   // ---- query fragments: registers for the whole kernel ----
   uint4 qf[2][8];
@@ -226,20 +265,28 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
   float mrun[2] = {NEG_BIG, NEG_BIG}, srun[2] = {0.f, 0.f};   // STATS, in log2 units
   const int bpg = window / 32;                                 // q blocks per query head
   const int gcount = nqb / bpg;                                // query heads in this row chunk
+  // EMIT, window <= 64: a wave holds whole query heads, so it finishes the task
+  // aggregate itself and stores one partial group value per key (slot = wq).
+  const bool wave_groups = bpg <= 2;
+  const float inv_window = 1.f / float(window);
 
-  // fragment addresses inside a buffer: key tile 0, k-step ks
-  int foff[8];
-#pragma unroll
-  for (int ks = 0; ks < 8; ++ks) foff[ks] = col * 256 + (((2 * ks + half) ^ (col & 15)) << 4);
+  // fragment address inside a buffer, key tile 0: k-step ks is at fbase ^ (32 ks)
+  // (the slot swizzle only touches address bits 4-7, the k-step bits 5-7)
+  const int fbase = col * 256 + ((half ^ (col & 15)) << 4);
 
-  // Two accumulator sets.  STATS keeps one tile "pending" across macro tiles; a
-  // pending set full of -inf folds to exactly nothing (its maximum never wins and
-  // every 2^(-inf) is 0), so the first phase needs no special case.
+  // Two accumulator sets; one tile is always "pending" (its vector work runs behind
+  // the MFMAs of the next one).  STATS: a pending set full of -inf folds to exactly
+  // nothing (its maximum never wins, every 2^(-inf) is 0).  EMIT: the pending set
+  // of the very first phase is zeros and lands in a red[] buffer nobody reads.
   f32x16 acc[2][2];
   const float ninf = -__builtin_inff();
 #pragma unroll
-  for (int r = 0; r < 16; ++r) { acc[1][0][r] = ninf; acc[1][1][r] = ninf; }
+  for (int r = 0; r < 16; ++r) { acc[1][0][r] = EMIT ? 0.f : ninf; acc[1][1][r] = EMIT ? 0.f : ninf; }
 
+  auto load_frags = [&](uint4 (&kf)[8], const unsigned char* kp) {
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) kf[ks] = *reinterpret_cast<const uint4*>(kp + (fbase ^ (32 * ks)));
+  };
   auto mfma_tile = [&](f32x16 (&a)[2], const uint4 (&kf)[8]) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) { a[0][r] = 0.f; a[1][r] = 0.f; }
@@ -255,43 +302,106 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
       }
     }
   };
-  auto load_frags = [&](uint4 (&kf)[8], const unsigned char* kb, int kt) {
+  // EMIT: per-block task aggregates (both half-waves hold them) -> red[buf]
+  auto red_store = [&](const float (&v)[2], int buf, int kt) {
+    const int blk0 = wq * 2;
+    if (wave_groups) {
+      float part;
+      if (bpg == 2) {
+        const float tv = TASK_MAX ? fmaxf(v[0], v[1]) : v[0] + v[1];
+        part = blk0 < nqb ? (TASK_MAX ? fast_exp2(tv) : tv * inv_window) : 0.f;
+      } else {
+        const float s0 = blk0 < nqb ? (TASK_MAX ? fast_exp2(v[0]) : v[0] * inv_window) : 0.f;
+        const float s1 = blk0 + 1 < nqb ? (TASK_MAX ? fast_exp2(v[1]) : v[1] * inv_window) : 0.f;
+        part = group_max ? fmaxf(s0, s1) : s0 + s1;
+      }
+      if (half == 0) red[buf][wq][kt * 32 + col] = part;
+    } else {
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks)
-      kf[ks] = *reinterpret_cast<const uint4*>(kb + kt * 8192 + foff[ks]);
+      for (int qb = 0; qb < 2; ++qb)
+        if (half == 0 && blk0 + qb < nqb) red[buf][blk0 + qb][kt * 32 + col] = v[qb];
+    }
   };
-  auto emit_store = [&](const f32x16 (&a)[2], int cur, int kt) {
+  auto emit_store = [&](const f32x16 (&a)[2], int buf, int kt) {
+    float v[2];
+    v[0] = emit_fold<TASK_MAX>(a[0], c2, nl[0]);
+    v[1] = emit_fold<TASK_MAX>(a[1], c2, nl[1]);
+    red_store(v, buf, kt);
+  };
+  // EMIT: threads 0..127 turn red[buf] into the group value of one key each
+  auto epilogue = [&](int t, int keys) {
+    if ((int)threadIdx.x < keys) {
+      const int buf = t % 3;
+      float gacc = 0.f;
+      if (wave_groups) {
+        const int nw = (nqb + 1) >> 1;
+        for (int w = 0; w < nw; ++w) {
+          const float x = red[buf][w][threadIdx.x];
+          gacc = group_max ? fmaxf(gacc, x) : gacc + x;
+        }
+      } else {
+        for (int g = 0; g < gcount; ++g) {
+          float tv = TASK_MAX ? NEG_BIG : 0.f;
+          for (int j = 0; j < bpg; ++j) {
+            const float x = red[buf][g * bpg + j][threadIdx.x];
+            tv = TASK_MAX ? fmaxf(tv, x) : tv + x;
+          }
+          const float sv = TASK_MAX ? fast_exp2(tv) : tv * inv_window;
+          gacc = group_max ? fmaxf(gacc, sv) : gacc + sv;
+        }
+      }
+      out[((size_t)rc * hkv + h) * total + tok0 + key_begin + t * MF_TILE + threadIdx.x] = gacc;
+    }
+  };
+  // One key tile at a time with masking of keys past `keys_here` (ragged tile, or
+  // every tile when the wave has an odd number of key tiles).
+  auto serial_tile = [&](int t, int keys_here) {
+    const unsigned char* kb = kbuf[t & 1];
+    for (int j = 0; j < NT; ++j) {
+      const int kt = wk + j * WK;
+      if (kt * 32 >= keys_here) break;          // wave-uniform
+      uint4 kf[8];
+      load_frags(kf, kb + kt * 8192);
+      mfma_tile(acc[0], kf);
+      if (!EMIT) {
+        if (kt * 32 + 32 > keys_here) {      // keys past the sequence drop out
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-      const float v = emit_fold<TASK_MAX>(a[qb], c2, nl[qb]);
-      const int blk = wq * 2 + qb;
-      if (half == 0 && blk < nqb) red[cur][blk][kt * 32 + col] = v;
+          for (int r = 0; r < 16; ++r)
+            if (kt * 32 + acc_row(r, half) >= keys_here) { acc[0][0][r] = NEG_BIG; acc[0][1][r] = NEG_BIG; }
+        }
+        stats_fold(acc[0][0], c2, mrun[0], srun[0]);
+        stats_fold(acc[0][1], c2, mrun[1], srun[1]);
+      } else {
+        emit_store(acc[0], t % 3, kt);
+      }
     }
   };
 
-  // tile 0 must have landed
+  // tiles 0 and 1 have landed
   wait_vmcnt<0>();
   __syncthreads();
 
-  for (int it = 0; it < ntiles; ++it) {
-    const int cur = it & 1;
-    const int key0 = key_begin + it * MF_TILE;
-    if (it + 1 < ntiles) issue_tile(it + 1);   // its buffer was last read in iteration it-1
-    const unsigned char* kb = kbuf[cur];
-    const int keys_here = it < nfull ? MF_TILE : tail;
-
-    if (it < nfull && (NT % 2 == 0)) {
-      // ---- steady state: full tile, software-pipelined phases ----
-      // Phase j: the 16 MFMAs of key tile j go to accumulator set j&1; behind MFMA i
-      // comes slice i of the vector work on the other set (the previous tile) and,
-      // after both MFMAs of a k-step, the fragment of that k-step for the next tile.
-      uint4 kf[8];
-      load_frags(kf, kb, wk);
+  if (PIPE) {
+    uint4 kf[8];
+    load_frags(kf, kbuf[0] + wk * 8192);
+    for (int it = 0; it < nfull; ++it) {
+      const unsigned char* kb = kbuf[it & 1];
 #pragma unroll
       for (int j = 0; j < NT; ++j) {
         const int kt = wk + j * WK;
         const int p = j & 1;
-        const bool overlap = !EMIT || j > 0;     // EMIT starts every macro tile with no pending tile
+        const unsigned char* nkb;       // fragments to prefetch during this phase
+        if (j + 1 < NT) {
+          nkb = kb + (kt + WK) * 8192;
+        } else {
+          // all fragments of tile `it` are in registers: hand its buffer over
+          if (it + 1 < ntiles) wait_vmcnt<0>();
+          __syncthreads();
+          if (EMIT && it > 0) epilogue(it - 1, MF_TILE);
+          if (it + 2 < ntiles) issue_tile(it + 2);
+          // next full tile's first fragments (or a harmless re-read of this tile's)
+          nkb = (it + 1 < nfull ? kbuf[(it + 1) & 1] : kb) + wk * 8192;
+        }
         StatsCarry carry;
         float ev[2];
         const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -304,78 +414,49 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
             acc[p][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(qf[qb][ks]), kfr, cin, 0, 0, 0);
           else        // rows = keys, columns = queries
             acc[p][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr, as_bf16x8(qf[qb][ks]), cin, 0, 0, 0);
-          if (qb == 1 && j + 1 < NT)
-            kf[ks] = *reinterpret_cast<const uint4*>(kb + (kt + WK) * 8192 + foff[ks]);
-          if (overlap) {
-            if (!EMIT) stats_slice(i, acc[p ^ 1][0], acc[p ^ 1][1], c2, mrun, srun, carry);
-            else emit_slice<TASK_MAX>(i, acc[p ^ 1][0], acc[p ^ 1][1], c2, nl, ev);
-          }
+          if (qb == 1) kf[ks] = *reinterpret_cast<const uint4*>(nkb + (fbase ^ (32 * ks)));
+          if (!EMIT) stats_slice(i, acc[p ^ 1][0], acc[p ^ 1][1], c2, mrun, srun, carry);
+          else emit_slice<TASK_MAX>(i, acc[p ^ 1][0], acc[p ^ 1][1], c2, nl, ev);
           __builtin_amdgcn_sched_barrier(0);
         }
-        if (EMIT && overlap) {
-#pragma unroll
-          for (int qb = 0; qb < 2; ++qb) {
-            const int blk = wq * 2 + qb;
-            if (half == 0 && blk < nqb) red[cur][blk][(kt - WK) * 32 + col] = ev[qb];
-          }
-        }
-      }
-      if (EMIT) emit_store(acc[(NT - 1) & 1], cur, wk + (NT - 1) * WK);
-    } else {
-      // ---- ragged tile (always the last) or NT == 1: one key tile at a time ----
-      if (!EMIT && (NT % 2 == 0)) {   // flush the pending tile first
-        stats_fold(acc[1][0], c2, mrun[0], srun[0]);
-        stats_fold(acc[1][1], c2, mrun[1], srun[1]);
-#pragma unroll
-        for (int r = 0; r < 16; ++r) { acc[1][0][r] = ninf; acc[1][1][r] = ninf; }
-      }
-      for (int j = 0; j < NT; ++j) {
-        const int kt = wk + j * WK;
-        if (kt * 32 >= keys_here) break;          // wave-uniform
-        uint4 kf[8];
-        load_frags(kf, kb, kt);
-        mfma_tile(acc[0], kf);
-        if (!EMIT) {
-          if (kt * 32 + 32 > keys_here) {      // keys past the sequence drop out
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-              if (kt * 32 + acc_row(r, half) >= keys_here) { acc[0][0][r] = NEG_BIG; acc[0][1][r] = NEG_BIG; }
-          }
-          stats_fold(acc[0][0], c2, mrun[0], srun[0]);
-          stats_fold(acc[0][1], c2, mrun[1], srun[1]);
-        } else {
-          emit_store(acc[0], cur, kt);
+        if (EMIT) {
+          // the pending tile: previous key tile of this macro tile, or the last
+          // key tile of the previous one (tile -1 goes to a buffer nobody reads)
+          const int ptile = j == 0 ? it + 2 : it;            // == it - 1 (mod 3) for j == 0
+          const int pkt = j == 0 ? wk + (NT - 1) * WK : kt - WK;
+          red_store(ev, ptile % 3, pkt);
         }
       }
     }
-
-    // tile it+1 must have landed before anyone reads it
-    wait_vmcnt<0>();
-    __syncthreads();
-
-    if (EMIT) {
-      // threads 0..127: one key each; combine q blocks -> task -> group
-      if ((int)threadIdx.x < keys_here) {
-        float gacc = 0.f;
-        for (int g = 0; g < gcount; ++g) {
-          float tv = TASK_MAX ? NEG_BIG : 0.f;
-          for (int j = 0; j < bpg; ++j) {
-            const float x = red[cur][g * bpg + j][threadIdx.x];
-            tv = TASK_MAX ? fmaxf(tv, x) : tv + x;
-          }
-          const float sv = TASK_MAX ? fast_exp2(tv) : tv / float(window);
-          gacc = group_max ? fmaxf(gacc, sv) : gacc + sv;
-        }
-        out[((size_t)rc * hkv + h) * total + tok0 + key0 + threadIdx.x] = gacc;
-      }
+    // the last key tile of the last full macro tile is still pending
+    if (!EMIT) {
+      stats_fold(acc[1][0], c2, mrun[0], srun[0]);
+      stats_fold(acc[1][1], c2, mrun[1], srun[1]);
+    } else if (nfull > 0) {
+      emit_store(acc[1], (nfull - 1) % 3, wk + (NT - 1) * WK);
+    }
+    if (tail > 0) {
+      wait_vmcnt<0>();
+      __syncthreads();
+      if (EMIT && nfull > 0) epilogue(nfull - 1, MF_TILE);
+      serial_tile(nfull, tail);
+      __syncthreads();
+      if (EMIT) epilogue(nfull, tail);
+    } else {
+      __syncthreads();
+      if (EMIT && nfull > 0) epilogue(nfull - 1, MF_TILE);
+    }
+  } else {
+    for (int it = 0; it < ntiles; ++it) {
+      serial_tile(it, it < nfull ? MF_TILE : tail);
+      wait_vmcnt<0>();
+      __syncthreads();
+      if (it + 2 < ntiles) issue_tile(it + 2);
+      if (EMIT) epilogue(it, it < nfull ? MF_TILE : tail);
     }
   }
 
   if (!EMIT) {
-    if (NT % 2 == 0) {   // the tile still pending
-      stats_fold(acc[1][0], c2, mrun[0], srun[0]);
-      stats_fold(acc[1][1], c2, mrun[1], srun[1]);
-    }
     // lanes l and l+32 hold the same query over different keys
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {

@@ -312,3 +312,14 @@ def test_batch_packing_independence():
     np.testing.assert_array_equal(packed["S"][:, :, lo:hi], alone["S"])
     np.testing.assert_array_equal(packed["idx"][:, :, lo:hi], alone["idx"])
     np.testing.assert_array_equal(packed["lengths"][b], alone["lengths"][0])
+
+
+def test_copy_probe_copies():
+    _say("copy probe")
+    src = torch.arange(1 << 20, dtype=torch.int32, device="cuda")
+    dst = torch.zeros_like(src)
+    kv.kvc_copy_probe(dst.data_ptr(), src.data_ptr(), src.numel() * 4, stream())
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
+    with pytest.raises(kv.KvcError):
+        kv.kvc_copy_probe(dst.data_ptr(), src.data_ptr(), 10, stream())
