@@ -22,6 +22,10 @@ import numpy as np  # noqa: E402
 METRIC = "context tokens compressed/sec at Llama-3-8B shape, L=128k"
 PEAK_BF16_MFMA_TFLOPS = 2500.0
 PEAK_HBM_GBPS = 8000.0
+# HBM bytes per launch of the score kernels at the config-2 layer shape (32/8 heads, d=128,
+# N=131072, M=64), from rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by the copy-probe factors
+# (2.000 / 1.000); source: profiles/score_mfma_config2_hbm_traffic.md
+MEASURED_TRAFFIC_BYTES = {"score_mfma<stats>": 281.7e6, "score_mfma<emit>": 278.8e6}
 
 
 def log(msg):
@@ -188,9 +192,11 @@ def main():
         c, ms = per_step[dom]
         avg_s = ms / c * 1e-3
         achieved = flops_per_launch / avg_s / 1e12
+        layer_shape = (cfg.hq, cfg.hkv, cfg.head_dim, cfg.window, total) == (32, 8, 128, 64, 131072)
         roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved,
                     "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
-                    "frac": achieved / PEAK_BF16_MFMA_TFLOPS, "traffic": None,
+                    "frac": achieved / PEAK_BF16_MFMA_TFLOPS,
+                    "traffic": MEASURED_TRAFFIC_BYTES.get(dom) if layer_shape else None,
                     "avg_launch_us": avg_s * 1e6, "launches_per_step": c}
     stages = {
         "score_ms": sum(ms for k, (c, ms) in per_step.items() if k.startswith("score")),
