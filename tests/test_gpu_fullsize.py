@@ -1,9 +1,11 @@
-"""Full-size check of the headline workload (config 2: 32 layers, 32/8 heads, d=128,
-N=131072, M=64, bf16, keep 10 %) in the launch configuration bench.py times.
+"""Full-size checks of the BASELINE workloads in the launch configuration bench.py
+times (config 2 is the benchmarked one; 1, 3 and 4 exercise the 32k shape, the packed
+variable-length batch and the deep GQA-8 shape with row chunks).
 
-The oracle cannot run the whole pass at this size in test time, so:
-* two sampled layers are scored by the oracle in full and compared with the GPU
-  (scores within the tolerance; selected sets under the near-threshold exemption);
+The oracle cannot run a whole pass at these sizes in test time, so:
+* a few sampled (sequence, layer) pairs are scored by the oracle in full and compared
+  with the GPU (scores within the tolerance; selected sets under the near-threshold
+  exemption);
 * everything else is checked through properties that hold at any size (idx is a
   permutation, S' = S[idx] is non-increasing with index-ascending ties, I is the head
   mean, tau is the budget-th largest pool entry, lengths follow the tie rule and sum
@@ -21,41 +23,60 @@ from oracle import kvc_oracle as orc
 from kvc_testlib import EPS, to_dev
 
 pytestmark = pytest.mark.gpu
-SAMPLED_LAYERS = (5, 31)
+
+CASES = {
+    # config id: sampled (sequence, layer) pairs scored by the oracle
+    1: [(0, 0), (0, 17)],
+    2: [(0, 5), (0, 31)],
+    3: [(0, 3), (5, 30)],
+    4: [(0, 79)],
+}
 
 
-def test_config2_full_size():
-    cfg = wl.get_config(2)
-    n, lyr, hkv, d = cfg.n, cfg.layers, cfg.hkv, cfg.head_dim
-    budget = wl.budget_for(cfg, n)
-    print(f"[case] full-size config 2: N={n} layers={lyr} budget={budget}", flush=True)
+@pytest.mark.parametrize("cid", sorted(CASES))
+def test_full_size(cid):
+    cfg = wl.get_config(cid)
+    lyr, hkv, d, bt = cfg.layers, cfg.hkv, cfg.head_dim, cfg.batch
+    lens = wl.seq_lens(cfg, 0)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    total = int(cu[-1])
+    budgets = [wl.budget_for(cfg, int(n)) for n in lens]
+    tb = sum(budgets)
+    sampled = CASES[cid]
+    print(f"[case] full-size config {cid}: lens={lens.tolist()} layers={lyr} budgets={budgets}",
+          flush=True)
 
     def gen(l):
-        return (l,) + wl.make_layer(cfg, 0, 0, l, n)
+        qs, ks, vs = [], [], []
+        for b in range(bt):
+            q, k, v = wl.make_layer(cfg, 0, b, l, int(lens[b]))
+            qs.append(q); ks.append(k); vs.append(v)
+        keep = {b: (qs[b], ks[b]) for (b, ll) in sampled if ll == l}
+        return l, np.stack(qs), np.concatenate(ks, axis=1), np.concatenate(vs, axis=1), keep
 
     q_dev, k_dev, v_dev = [None] * lyr, [None] * lyr, [None] * lyr
     host = {}
     with cf.ThreadPoolExecutor(max_workers=16) as pool:
-        for l, q, k, v in pool.map(gen, range(lyr)):
-            q_dev[l], k_dev[l], v_dev[l] = to_dev(q[None]), to_dev(k), to_dev(v)
-            if l in SAMPLED_LAYERS:
-                host[l] = (q, k)
+        for l, q, k, v, keep in pool.map(gen, range(lyr)):
+            q_dev[l], k_dev[l], v_dev[l] = to_dev(q), to_dev(k), to_dev(v)
+            for b, qk in keep.items():
+                host[(b, l)] = qk
     print("[case] inputs resident", flush=True)
 
-    p = kv.KvcParams(1, lyr, cfg.hq, hkv, d, cfg.window, kv.KVC_BF16)
-    ws_bytes = kv.kvc_workspace_size(p, n, n)
+    p = kv.KvcParams(bt, lyr, cfg.hq, hkv, d, cfg.window, kv.KVC_BF16)
+    ws_bytes = kv.kvc_workspace_size(p, total, int(lens.max()))
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
-    k_out = torch.zeros(budget * hkv * d, dtype=torch.bfloat16, device="cuda")
+    k_out = torch.zeros(tb * hkv * d, dtype=torch.bfloat16, device="cuda")
     v_out = torch.zeros_like(k_out)
-    lengths = torch.full((lyr,), -1, dtype=torch.int32, device="cuda")
-    offsets = torch.full((lyr + 1,), -1, dtype=torch.int64, device="cuda")
-    S = torch.zeros((lyr, hkv, n), dtype=torch.float32, device="cuda")
-    idx = torch.zeros((lyr, hkv, n), dtype=torch.int32, device="cuda")
+    lengths = torch.full((bt * lyr,), -1, dtype=torch.int32, device="cuda")
+    offsets = torch.full((bt * lyr + 1,), -1, dtype=torch.int64, device="cuda")
+    S = torch.zeros((lyr, hkv, total), dtype=torch.float32, device="cuda")
+    idx = torch.zeros((lyr, hkv, total), dtype=torch.int32, device="cuda")
     ss = torch.zeros_like(S)
-    I = torch.zeros((lyr, n), dtype=torch.float32, device="cuda")
-    tau = torch.zeros(1, dtype=torch.float32, device="cuda")
+    I = torch.zeros((lyr, total), dtype=torch.float32, device="cuda")
+    tau = torch.zeros(bt, dtype=torch.float32, device="cuda")
     kv.kvc_compress(p, [t.data_ptr() for t in q_dev], [t.data_ptr() for t in k_dev],
-                    [t.data_ptr() for t in v_dev], [0, n], [budget], k_out.data_ptr(),
+                    [t.data_ptr() for t in v_dev], cu, budgets, k_out.data_ptr(),
                     v_out.data_ptr(), lengths.data_ptr(), offsets.data_ptr(), ws.data_ptr(),
                     ws_bytes, torch.cuda.current_stream().cuda_stream, scores=S.data_ptr(),
                     idx=idx.data_ptr(), s_sorted=ss.data_ptr(), composite=I.data_ptr(),
@@ -63,55 +84,64 @@ def test_config2_full_size():
     torch.cuda.synchronize()
     print("[case] compress done", flush=True)
 
-    # ---- properties at full size (GPU-side arithmetic is plain torch) ----
-    idx64 = idx.long()
-    assert torch.equal(torch.sort(idx64, dim=-1).values,
-                       torch.arange(n, device="cuda").expand(lyr, hkv, n))
-    assert torch.equal(ss, torch.gather(S, 2, idx64))
-    dif = ss[..., 1:] - ss[..., :-1]
-    assert bool((dif <= 0).all())
-    tie = dif == 0
-    assert bool(((idx64[..., 1:] - idx64[..., :-1])[tie] > 0).all())       # ties: ascending index
-    mean = ss.double().sum(dim=1) / hkv        # fp32 sum of 8 positives + divide: <= 8 roundings
-    assert bool(((I.double() - mean).abs() <= 8 * 2.0 ** -24 * mean).all())
-    assert bool((I[:, 1:] <= I[:, :-1]).all())
-    pool = I.reshape(-1)
-    kth = torch.topk(pool, budget, sorted=True).values[-1]
-    assert tau.item() == kth.item()
-    gt = (I > kth).sum(dim=1)
-    eq = (I == kth).sum(dim=1)
-    left = budget - int(gt.sum())
-    expect = []
-    for l in range(lyr):
-        take = min(int(eq[l]), left)
-        left -= take
-        expect.append(int(gt[l]) + take)
-    lens = lengths.cpu().tolist()
-    assert lens == expect and sum(lens) == budget
-    offs = offsets.cpu().tolist()
-    assert offs == [0] + np.cumsum(lens).tolist()
-    for l in range(lyr):                                                   # bit copies
-        nl, base = lens[l], offs[l] * hkv * d
-        sel = idx64[l, :, :nl, None].expand(hkv, nl, d)
-        for src, dst in ((k_dev[l], k_out), (v_dev[l], v_out)):
-            ref = torch.gather(src.view(torch.int16), 1, sel)
-            got = dst.view(torch.int16)[base: base + hkv * nl * d].view(hkv, nl, d)
-            assert torch.equal(ref, got), f"layer {l}"
+    # ---- properties at full size (plain torch arithmetic on the device) ----
+    lens_g = lengths.cpu().numpy().reshape(bt, lyr)
+    offs = offsets.cpu().numpy()
+    assert offs.tolist() == [0] + np.cumsum(lens_g.reshape(-1)).tolist()
+    tau_h = tau.cpu().numpy()
+    for b in range(bt):
+        lo, hi = int(cu[b]), int(cu[b + 1])
+        n = hi - lo
+        idx_b = idx[:, :, lo:hi].long()
+        S_b, ss_b, I_b = S[:, :, lo:hi], ss[:, :, lo:hi], I[:, lo:hi]
+        assert torch.equal(torch.sort(idx_b, dim=-1).values,
+                           torch.arange(n, device="cuda").expand(lyr, hkv, n))
+        assert torch.equal(ss_b, torch.gather(S_b, 2, idx_b))
+        dif = ss_b[..., 1:] - ss_b[..., :-1]
+        assert bool((dif <= 0).all())
+        assert bool(((idx_b[..., 1:] - idx_b[..., :-1])[dif == 0] > 0).all())   # ties ascending
+        mean = ss_b.double().sum(dim=1) / hkv      # fp32 sum of 8 positives + divide
+        assert bool(((I_b.double() - mean).abs() <= 8 * 2.0 ** -24 * mean).all())
+        assert bool((I_b[:, 1:] <= I_b[:, :-1]).all())
+        kth = torch.topk(I_b.reshape(-1), budgets[b], sorted=True).values[-1]
+        assert tau_h[b] == kth.item()
+        gt = (I_b > kth).sum(dim=1).cpu().numpy()
+        eq = (I_b == kth).sum(dim=1).cpu().numpy()
+        left = budgets[b] - int(gt.sum())
+        expect = []
+        for l in range(lyr):
+            take = min(int(eq[l]), left)
+            left -= take
+            expect.append(int(gt[l]) + take)
+        assert lens_g[b].tolist() == expect and sum(expect) == budgets[b]
+        for l in range(lyr):                                                  # bit copies
+            nl, base = int(lens_g[b, l]), int(offs[b * lyr + l]) * hkv * d
+            sel = (idx_b[l, :, :nl, None] + lo).expand(hkv, nl, d)
+            for src, dst in ((k_dev[l], k_out), (v_dev[l], v_out)):
+                ref = torch.gather(src.view(torch.int16), 1, sel)
+                got = dst.view(torch.int16)[base: base + hkv * nl * d].view(hkv, nl, d)
+                assert torch.equal(ref, got), f"sequence {b} layer {l}"
     print("[case] properties hold", flush=True)
 
-    # ---- oracle on the sampled layers ----
-    S_h, idx_h, lens_np = S.cpu().numpy(), idx.cpu().numpy(), np.array(lens)
-    for l in SAMPLED_LAYERS:
-        q, k = host[l]
+    # ---- oracle on the sampled (sequence, layer) pairs ----
+    for (b, l) in sampled:
+        lo, hi = int(cu[b]), int(cu[b + 1])
+        n = hi - lo
+        q, k = host[(b, l)]
         ref = orc.score_layer(orc.widen(q), orc.widen(k))
-        err = np.abs(S_h[l] - ref) / ref
-        print(f"[case] layer {l}: worst relative score error {err.max():.3e}", flush=True)
+        got = S[l, :, lo:hi].cpu().numpy()
+        err = np.abs(got - ref) / ref
+        print(f"[case] sequence {b} layer {l}: worst relative score error {err.max():.3e}",
+              flush=True)
         assert err.max() <= EPS and err.max() <= 1e-4
-        nl = int(lens_np[l])
+        nl = int(lens_g[b, l])
+        if nl == 0:
+            continue
         _, ref_sorted = orc.head_rank(ref)
+        idx_h = idx[l, :, lo:lo + nl].cpu().numpy()
         for h in range(hkv):
             t = ref_sorted[h, nl - 1]
             chosen = np.zeros(n, dtype=bool)
-            chosen[idx_h[l, h, :nl]] = True
+            chosen[idx_h[h]] = True
             assert chosen[ref[h] > t * (1 + EPS)].all()
             assert not chosen[ref[h] < t * (1 - EPS)].any()
