@@ -233,8 +233,9 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
     const int blk = wq * 2 + qb;
     const int r = row0 + blk * 32 + col;
     const bool ok = blk < nqb;
-    const int g = ok ? r / window : 0, m = ok ? r % window : 0;
-    const size_t qrow = ((size_t)b * hq + h * group + g) * window + m;
+    // the G query heads of a KV head are contiguous, so row r of the group is
+    // simply row r after the group's first query row
+    const size_t qrow = ((size_t)b * hq + h * group) * window + (ok ? r : 0);
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
       uint4 v = make_uint4(0, 0, 0, 0);
@@ -255,7 +256,7 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
         float v = 0.f;
         if (ok) {
           const int rr = row0 + blk * 32 + acc_row(r, half);
-          v = -lse2[((size_t)b * hq + h * group + rr / window) * window + rr % window];
+          v = -lse2[((size_t)b * hq + h * group) * window + rr];
         }
         nl[qb][r] = v;
       }
@@ -384,7 +385,12 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
   if (PIPE) {
     uint4 kf[8];
     load_frags(kf, kbuf[0] + wk * 8192);
+    // Two workgroups share a CU and the hardware favours the older one; alternating
+    // the wave priority per tile keeps them advancing at the same pace.
+    const int prio_phase = (blockIdx.y * 2 >= gridDim.y) ? 1 : 0;
     for (int it = 0; it < nfull; ++it) {
+      if ((it + prio_phase) & 1) __builtin_amdgcn_s_setprio(1);
+      else __builtin_amdgcn_s_setprio(0);
       const unsigned char* kb = kbuf[it & 1];
 #pragma unroll
       for (int j = 0; j < NT; ++j) {
@@ -428,6 +434,7 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
         }
       }
     }
+    __builtin_amdgcn_s_setprio(0);
     // the last key tile of the last full macro tile is still pending
     if (!EMIT) {
       stats_fold(acc[1][0], c2, mrun[0], srun[0]);
@@ -480,7 +487,7 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
       for (int k2 = 0; k2 < WK; ++k2)
         ss += stat[k2 * WQ + sq][qb][j][1] * fast_exp2(stat[k2 * WQ + sq][qb][j][0] - mm);
       const int r = row0 + blk * 32 + j;
-      const size_t qrow = ((size_t)b * hq + h * group + r / window) * window + r % window;
+      const size_t qrow = ((size_t)b * hq + h * group) * window + r;
       // partial statistics are stored chunk-major so the merge reads coalesced
       const size_t rows_layer = (size_t)gridDim.z * hq * window;
       part_m[(size_t)blockIdx.x * rows_layer + qrow] = mm;
