@@ -174,6 +174,7 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
   __shared__ __attribute__((aligned(1024))) unsigned char kbuf[MF_NBUF][MF_KBUF];
   __shared__ float red[EMIT ? 3 : 1][8][EMIT ? MF_TILE : 1];   // EMIT: per (q block | wave, key)
   __shared__ float stat[EMIT ? 1 : 4][2][32][2];               // STATS: per wave (max, sum)
+  __shared__ __attribute__((aligned(16))) float lse_s[EMIT ? MF_RCHUNK : 4];   // EMIT: -lse2 of the row chunk
 
   const int b = blockIdx.z;
   const int tok0 = seq.cu[b], n = seq.cu[b + 1] - tok0;
@@ -224,7 +225,6 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
     }
   };
   issue_tile(0);
-  if (ntiles > 1) issue_tile(1);
 
   // ---- query fragments: registers for the whole kernel ----
   uint4 qf[2][8];
@@ -244,24 +244,11 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
     }
   }
 
-  // EMIT: minus lse2 of the 16 accumulator rows of each q block held by this lane
-  float nl[2][16];
-  if (EMIT) {
-#pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-      const int blk = wq * 2 + qb;
-      const bool ok = blk < nqb;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float v = 0.f;
-        if (ok) {
-          const int rr = row0 + blk * 32 + acc_row(r, half);
-          v = -lse2[((size_t)b * hq + h * group) * window + rr];
-        }
-        nl[qb][r] = v;
-      }
-    }
-  }
+  // EMIT: minus lse2 of this row chunk goes through LDS (one coalesced load)
+  float my_nl = 0.f;
+  if (EMIT && (int)threadIdx.x < nqb * 32)
+    my_nl = -lse2[((size_t)b * hq + h * group) * window + row0 + threadIdx.x];
+  float nl[2][16];   // EMIT: minus lse2 of the lane's accumulator rows, filled after the first barrier
 
   float mrun[2] = {NEG_BIG, NEG_BIG}, srun[2] = {0.f, 0.f};   // STATS, in log2 units
   const int bpg = window / 32;                                 // q blocks per query head
@@ -330,28 +317,43 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
     red_store(v, buf, kt);
   };
   // EMIT: threads 0..127 turn red[buf] into the group value of one key each
+  // (even tiles: waves 0-1, odd tiles: waves 2-3, so the extra work is shared)
   auto epilogue = [&](int t, int keys) {
-    if ((int)threadIdx.x < keys) {
+    const int ekey = threadIdx.x & (MF_TILE - 1);
+    if ((int)(threadIdx.x >> 7) == (t & 1) && ekey < keys) {
       const int buf = t % 3;
-      float gacc = 0.f;
+      // all partials are read before any is used (one LDS round trip, not eight)
+      const int nslots = wave_groups ? (nqb + 1) >> 1 : nqb;
+      const float neutral = (!wave_groups && TASK_MAX) ? NEG_BIG : 0.f;
+      float x[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) x[i] = i < nslots ? red[buf][i][ekey] : neutral;
+      float gacc;
       if (wave_groups) {
-        const int nw = (nqb + 1) >> 1;
-        for (int w = 0; w < nw; ++w) {
-          const float x = red[buf][w][threadIdx.x];
-          gacc = group_max ? fmaxf(gacc, x) : gacc + x;
-        }
+        // finished group partials of the waves, all >= 0, so 0 is neutral for max and sum
+        gacc = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) gacc = group_max ? fmaxf(gacc, x[i]) : gacc + x[i];
       } else {
-        for (int g = 0; g < gcount; ++g) {
-          float tv = TASK_MAX ? NEG_BIG : 0.f;
-          for (int j = 0; j < bpg; ++j) {
-            const float x = red[buf][g * bpg + j][threadIdx.x];
-            tv = TASK_MAX ? fmaxf(tv, x) : tv + x;
+        // a query head spans 4 or 8 blocks: two heads of 4, or one of 8
+        float t0 = x[0], t1 = x[4];
+#pragma unroll
+        for (int i = 1; i < 4; ++i) {
+          t0 = TASK_MAX ? fmaxf(t0, x[i]) : t0 + x[i];
+          t1 = TASK_MAX ? fmaxf(t1, x[4 + i]) : t1 + x[4 + i];
+        }
+        if (bpg == 8) {
+          const float tv = TASK_MAX ? fmaxf(t0, t1) : t0 + t1;
+          gacc = TASK_MAX ? fast_exp2(tv) : tv * inv_window;
+        } else {
+          gacc = TASK_MAX ? fast_exp2(t0) : t0 * inv_window;
+          if (gcount > 1) {
+            const float s1 = TASK_MAX ? fast_exp2(t1) : t1 * inv_window;
+            gacc = group_max ? fmaxf(gacc, s1) : gacc + s1;
           }
-          const float sv = TASK_MAX ? fast_exp2(tv) : tv * inv_window;
-          gacc = group_max ? fmaxf(gacc, sv) : gacc + sv;
         }
       }
-      out[((size_t)rc * hkv + h) * total + tok0 + key_begin + t * MF_TILE + threadIdx.x] = gacc;
+      out[((size_t)rc * hkv + h) * total + tok0 + key_begin + t * MF_TILE + ekey] = gacc;
     }
   };
   // One key tile at a time with masking of keys past `keys_here` (ragged tile, or
@@ -378,9 +380,29 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
     }
   };
 
-  // tiles 0 and 1 have landed
+  // Tile 0 has landed (and the query fragments); tile 1 is requested only now, so
+  // that at kernel start, when every workgroup asks at once, all first tiles are
+  // served before any second one.
   wait_vmcnt<0>();
+  if (EMIT) lse_s[threadIdx.x] = my_nl;
+  if (ntiles > 1) issue_tile(1);
   __syncthreads();
+
+  // EMIT: minus lse2 of the 16 accumulator rows of each q block held by this lane
+  // (register r is row 8 (r/4) + 4 half + r%4: four consecutive rows per 16 bytes)
+  if (EMIT) {
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      const int blk = wq * 2 + qb;
+      const bool ok = blk < nqb;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (ok) v = *reinterpret_cast<const float4*>(&lse_s[blk * 32 + 8 * i + 4 * half]);
+        nl[qb][4 * i + 0] = v.x; nl[qb][4 * i + 1] = v.y; nl[qb][4 * i + 2] = v.z; nl[qb][4 * i + 3] = v.w;
+      }
+    }
+  }
 
   if (PIPE) {
     uint4 kf[8];
