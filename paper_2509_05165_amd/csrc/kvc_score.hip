@@ -216,12 +216,17 @@ __global__ __launch_bounds__(256) void score_merge(SeqTable seq, int rows_per_se
 
 // ---------------------------------------------------------------------------
 // finish: combine row-chunk partials, normalise the group mean, add head mean.
-// One thread per token; in place when part == S and row_chunks == 1.
+// One thread per token; in place when part == S and row_chunks == 1.  blockIdx.y
+// is a layer: both pointers advance by layer_stride floats per layer (one launch
+// can finish all layers when they were emitted in place).
 // ---------------------------------------------------------------------------
 __global__ void score_finish(const float* part, int row_chunks, int hkv, int total,
-                             float group_norm, int group_max, int add_head_mean, float* S) {
+                             float group_norm, int group_max, int add_head_mean, float* S,
+                             size_t layer_stride) {
   const int c = blockIdx.x * blockDim.x + threadIdx.x;
   if (c >= total) return;
+  part += blockIdx.y * layer_stride;
+  S += blockIdx.y * layer_stride;
   float sum = 0.f;
   float vals[8];
   for (int h0 = 0; h0 < hkv; h0 += 8) {
@@ -362,10 +367,15 @@ kvc_status launch_score(const Problem& pb, const void* const* q, const void* con
             group_max, part));
       }
     }
-    KVC_LAUNCH("score_finish", stream, score_finish<<<(total + 255) / 256, 256, 0, stream>>>(part, L.row_chunks, pb.hkv, total,
-                                                          group_norm, group_max,
-                                                          pb.add_head_mean, S_l));
+    // with separate partials each layer is finished before the next one reuses them
+    if (separate)
+      KVC_LAUNCH("score_finish", stream, score_finish<<<(total + 255) / 256, 256, 0, stream>>>(
+          part, L.row_chunks, pb.hkv, total, group_norm, group_max, pb.add_head_mean, S_l, 0));
   }
+  // emitted in place: one launch finishes every layer
+  if (!separate && pb.layers > 0 && total > 0)
+    KVC_LAUNCH("score_finish", stream, score_finish<<<dim3((total + 255) / 256, pb.layers), 256, 0, stream>>>(
+        S, 1, pb.hkv, total, group_norm, group_max, pb.add_head_mean, S, size_t(pb.hkv) * total));
   return KVC_OK;
 }
 

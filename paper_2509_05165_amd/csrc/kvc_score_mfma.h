@@ -443,8 +443,17 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
           else        // rows = keys, columns = queries
             acc[p][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr, as_bf16x8(qf[qb][ks]), cin, 0, 0, 0);
           if (qb == 1) kf[ks] = *reinterpret_cast<const uint4*>(nkb + (fbase ^ (32 * ks)));
-          if (!EMIT) stats_slice(i, acc[p ^ 1][0], acc[p ^ 1][1], c2, mrun, srun, carry);
-          else emit_slice<TASK_MAX>(i, acc[p ^ 1][0], acc[p ^ 1][1], c2, nl, ev);
+          if (!EMIT) {
+            stats_slice(i, acc[p ^ 1][0], acc[p ^ 1][1], c2, mrun, srun, carry);
+            // The slice results feed nothing until the end of the tile, so without an
+            // anchor the optimiser sinks the whole slice past the tile barrier (all
+            // vector work of a tile would then run after its MFMAs, not beside them).
+            if (i < 2) asm volatile("" : "+v"(carry.amax[i]));
+            else if (i == 2) asm volatile("" : "+v"(carry.s[0]), "+v"(carry.s[1]), "+v"(carry.nmn[0]), "+v"(carry.nmn[1]));
+            else asm volatile("" : "+v"(carry.s[0]), "+v"(carry.s[1]), "+v"(carry.e[0]), "+v"(carry.e[1]));
+          } else {
+            emit_slice<TASK_MAX>(i, acc[p ^ 1][0], acc[p ^ 1][1], c2, nl, ev);
+          }
           __builtin_amdgcn_sched_barrier(0);
         }
         if (EMIT) {
