@@ -30,6 +30,22 @@ convention, stated in the C header):
 * The budget is an integer; B_total = floor((1-r) * Lyr * N) is evaluated by
   the caller.
 
+Variants beyond the default pass (each off unless asked for):
+
+* value-norm weighting (Appendix on value norms, "v-norm"): every entry of the
+  attention matrix of query head q is multiplied by the Euclidean norm of the
+  value vector of the same token in q's KV head, before any aggregation.
+* position order: the retained rows of a head are written in ascending token
+  position instead of rank order (the retained *set* is unchanged), so that a
+  100 % budget reproduces K and V bit for bit.
+* per-layer floor m (the paper does not exclude N_l = 0 and defines no floor;
+  this reading): ranks 0..m-1 of every layer are taken first, the rest of the
+  budget goes to the top of the remaining pool with the usual tie rule.
+* unstructured selection (Appendix on unstructured eviction): the head
+  aggregation is skipped, the pool holds all Lyr*Hkv*N rank-aligned scores,
+  the budget counts (head, token) entries and every head keeps its own prefix
+  N_{l,h}.  Ties by ascending flat index (l*Hkv + h)*N + k.
+
 Pins (tests/test_oracle_*.py): library softmax in the single-query special
 case, closed forms (identical keys), shift/permutation invariants, row-sum
 identities, one-hot limit, library stable argsort, brute-force enumeration of
@@ -78,13 +94,18 @@ def attention(q_rows: np.ndarray, keys: np.ndarray, scale: float) -> np.ndarray:
 
 
 def score_layer(q, k, *, agg_task=AGG_MAX, agg_group=AGG_MEAN, add_head_mean=True,
-                scale=None) -> np.ndarray:
+                scale=None, v=None) -> np.ndarray:
     """S[h, c] for one layer of one sequence.
 
     q: [Hq, M, d], k: [Hkv, N, d] (float64).  Follows, in order, the three
     equations of Section 3.2.2: aggregation over task tokens (eq. 14),
     aggregation over the query heads of a KV group (eq. 15) and the head-mean
     augmentation that follows them.
+
+    v: optional [Hkv, N, d] (float64).  When given, the attention matrix of
+    every query head is replaced by the weighted matrix of the value-norm
+    appendix (v-norm variant): A^(w)[m, c] = A[m, c] * ||V[h, c, :]||_2 with h
+    the KV head of the query head.
     """
     hq, m, d = q.shape
     hkv, n, _ = k.shape
@@ -94,6 +115,8 @@ def score_layer(q, k, *, agg_task=AGG_MAX, agg_group=AGG_MEAN, add_head_mean=Tru
     s_task = np.empty((hq, n))
     for qh in range(hq):
         a = attention(q[qh], k[qh // g], scale)       # [M, N]: A^(l, qh, c, m)
+        if v is not None:
+            a = a * np.sqrt((v[qh // g] * v[qh // g]).sum(axis=1))[None, :]   # A^(w)
         s_task[qh] = _agg(a, agg_task, axis=0)        # eq. 14
     s_group = _agg(s_task.reshape(hkv, g, n), agg_group, axis=1)   # eq. 15
     if add_head_mean:
@@ -129,7 +152,7 @@ def composite(s_sorted: np.ndarray, agg_head=AGG_MEAN) -> np.ndarray:
     return _agg(np.asarray(s_sorted, dtype=np.float64), agg_head, axis=0)
 
 
-def global_select(i_all: np.ndarray, budget: int):
+def global_select(i_all: np.ndarray, budget: int, min_per_layer: int = 0):
     """Per-layer lengths from the global pool (Section 3.3, pool / budget /
     N_l equations).
 
@@ -138,25 +161,51 @@ def global_select(i_all: np.ndarray, budget: int):
     N_l counts how many of the taken entries lie in layer l.  Returns
     (lengths int64 [Lyr], tau) with tau the smallest taken score (None when
     budget == 0).
+
+    min_per_layer = m > 0 (per-layer floor, a reading: the paper defines
+    none): ranks 0..min(m, N)-1 of every layer are taken unconditionally and
+    only the other pool entries compete for the rest of the budget; tau is
+    then the smallest score taken in that competition (None if nothing is
+    left to compete for).
+
+    The rows of i_all may as well be (layer, head) pairs holding rank-aligned
+    per-head scores: that is the unstructured variant's pool.
     """
     i_all = np.asarray(i_all)
     lyr, n = i_all.shape
-    if not 0 <= budget <= lyr * n:
+    floor = min(int(min_per_layer), n)
+    if floor < 0 or not lyr * floor <= budget <= lyr * n:
         raise ValueError("budget out of range")
     pool = i_all.reshape(-1)
-    order = np.lexsort((np.arange(pool.size), -pool))
-    taken = order[:budget]
-    lengths = np.bincount(taken // n, minlength=lyr).astype(np.int64)
-    tau = pool[taken[-1]] if budget > 0 else None
+    flat = np.arange(pool.size)
+    free = flat[(flat % n) >= floor]                  # entries that compete
+    order = free[np.lexsort((free, -pool[free]))]
+    taken = order[:budget - lyr * floor]
+    lengths = floor + np.bincount(taken // n, minlength=lyr).astype(np.int64)
+    tau = pool[taken[-1]] if taken.size > 0 else None
     return lengths, tau
 
 
-def gather(x: np.ndarray, idx: np.ndarray, n_keep: int) -> np.ndarray:
-    """X'[h, k, :] = X[h, idx[h, k], :], k < n_keep (final selection equations)."""
+def gather(x: np.ndarray, idx: np.ndarray, n_keep: int, position_order: bool = False) -> np.ndarray:
+    """X'[h, k, :] = X[h, idx[h, k], :], k < n_keep (final selection equations).
+
+    position_order: the same retained set idx[h, :n_keep] of every head, but
+    written in ascending token position."""
     hkv = x.shape[0]
     out = np.empty((hkv, n_keep) + x.shape[2:], dtype=x.dtype)
     for h in range(hkv):
-        out[h] = x[h, idx[h, :n_keep]]
+        rows = idx[h, :n_keep]
+        out[h] = x[h, np.sort(rows) if position_order else rows]
+    return out
+
+
+def gather_heads(x: np.ndarray, idx: np.ndarray, n_keep, position_order: bool = False) -> list:
+    """Unstructured variant: head h keeps its own prefix idx[h, :n_keep[h]].
+    Returns a list of Hkv arrays [n_keep[h], d]."""
+    out = []
+    for h in range(x.shape[0]):
+        rows = idx[h, :int(n_keep[h])]
+        out.append(x[h, np.sort(rows) if position_order else rows])
     return out
 
 
@@ -164,29 +213,51 @@ def gather(x: np.ndarray, idx: np.ndarray, n_keep: int) -> np.ndarray:
 # whole pass for one sequence
 # --------------------------------------------------------------------------
 def compress(q_layers, k_layers, v_layers, budget: int, *, agg_task=AGG_MAX,
-             agg_group=AGG_MEAN, agg_head=AGG_MEAN, add_head_mean=True, scale=None):
+             agg_group=AGG_MEAN, agg_head=AGG_MEAN, add_head_mean=True, scale=None,
+             value_norm=False, position_order=False, min_per_layer=0, unstructured=False):
     """Run the pass on one sequence.
 
     q_layers[l]: [Hq, M, d]; k_layers[l], v_layers[l]: [Hkv, N, d]; any of
     float32 / float64 / bf16 bits (uint16).  K' and V' keep the input dtype
     (bit copies).  Returns a dict with every intermediate.
+
+    unstructured: budget counts (head, token) entries; "lengths" is [Lyr, Hkv],
+    "I" is None and K_out[l] / V_out[l] are lists of per-head arrays.
     """
     lyr = len(k_layers)
     s_all, idx_all, ssorted_all, i_all = [], [], [], []
     for l in range(lyr):
         s = score_layer(widen(q_layers[l]), widen(k_layers[l]), agg_task=agg_task,
-                        agg_group=agg_group, add_head_mean=add_head_mean, scale=scale)
+                        agg_group=agg_group, add_head_mean=add_head_mean, scale=scale,
+                        v=widen(v_layers[l]) if value_norm else None)
         idx, s_sorted = head_rank(s)
         s_all.append(s)
         idx_all.append(idx)
         ssorted_all.append(s_sorted)
         i_all.append(composite(s_sorted, agg_head))
     i_all = np.stack(i_all)
-    lengths, tau = global_select(i_all, budget)
-    k_out = [gather(np.asarray(k_layers[l]), idx_all[l], int(lengths[l])) for l in range(lyr)]
+    if unstructured:
+        s3 = np.stack(ssorted_all)                                   # [Lyr, Hkv, N]
+        hkv, n = s3.shape[1], s3.shape[2]
+        flat_len, tau = global_select(s3.reshape(lyr * hkv, n), budget, min_per_layer)
+        lengths = flat_len.reshape(lyr, hkv)
+        k_out = [gather_heads(np.asarray(k_layers[l]), idx_all[l], lengths[l], position_order)
+                 for l in range(lyr)]
+        v_out = None
+        if v_layers is not None:
+            v_out = [gather_heads(np.asarray(v_layers[l]), idx_all[l], lengths[l], position_order)
+                     for l in range(lyr)]
+        return {
+            "S": np.stack(s_all), "idx": np.stack(idx_all), "S_sorted": s3,
+            "I": None, "tau": tau, "lengths": lengths, "K_out": k_out, "V_out": v_out,
+        }
+    lengths, tau = global_select(i_all, budget, min_per_layer)
+    k_out = [gather(np.asarray(k_layers[l]), idx_all[l], int(lengths[l]), position_order)
+             for l in range(lyr)]
     v_out = None
     if v_layers is not None:
-        v_out = [gather(np.asarray(v_layers[l]), idx_all[l], int(lengths[l])) for l in range(lyr)]
+        v_out = [gather(np.asarray(v_layers[l]), idx_all[l], int(lengths[l]), position_order)
+                 for l in range(lyr)]
     return {
         "S": np.stack(s_all), "idx": np.stack(idx_all), "S_sorted": np.stack(ssorted_all),
         "I": i_all, "tau": tau, "lengths": lengths, "K_out": k_out, "V_out": v_out,
