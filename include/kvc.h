@@ -16,6 +16,11 @@
  *                         for V                          (Section 3.3, last eqs.)
  *   kvc_compress runs 1-5 back to back on one stream.
  *
+ * Variants, all off by default (kvc_params): value-norm weighting of the
+ * attention matrix (appendix on value norms), position-ordered output rows, a
+ * per-layer floor on N_l, and the unstructured selection of the appendix on
+ * unstructured eviction (no step 3; every head keeps its own prefix).
+ *
  * Conventions shared by every entry point
  * ---------------------------------------
  * Notation: Bt sequences, Lyr layers, Hq query heads, Hkv KV heads, G = Hq/Hkv,
@@ -47,7 +52,13 @@
  *               input dtype.  Block (b,l) is the dense tensor [Hkv, N_{b,l}, d]
  *               (the uniform per-layer layout of the problem statement,
  *               constraint C2) starting at element offsets[b*Lyr+l]*Hkv*d.
- *               Rows are in descending-importance (rank) order.
+ *               Rows are in descending-importance (rank) order, or in
+ *               ascending token position with KVC_ORDER_POSITION.
+ *   unstructured = 1: lengths is int32 [Bt*Lyr*Hkv] (N_{b,l,h}), offsets int64
+ *               [Bt*Lyr*Hkv+1]; block (b,l,h) is the dense tensor [N_{b,l,h}, d]
+ *               starting at element offsets[(b*Lyr+l)*Hkv+h]*d; the pools hold
+ *               (sum_b budget[b]) * d elements and budget[b] counts
+ *               (head, token) entries, 0 <= budget[b] <= Lyr*Hkv*N_b.
  *
  * Readings of the paper fixed by this library: no attention mask (each task
  * query sees all N_b cached keys of its sequence, softmax over exactly those);
@@ -87,6 +98,11 @@ typedef enum {
 
 typedef enum { KVC_F32 = 0, KVC_BF16 = 1 } kvc_dtype;
 typedef enum { KVC_AGG_MAX = 0, KVC_AGG_MEAN = 1 } kvc_agg;
+typedef enum {
+  KVC_ORDER_RANK = 0,    /* rows k_out[h,k,:] = K[h, idx[h,k], :]: the paper's literal order */
+  KVC_ORDER_POSITION = 1 /* the same retained rows of each head in ascending token position:
+                            a full budget then reproduces K and V bit for bit */
+} kvc_order;
 
 /* Problem description.  Defaults of the paper's experiments (Section 4.2):
  * agg_task = MAX, agg_group = MEAN, agg_head = MEAN, add_head_mean = 1. */
@@ -103,6 +119,17 @@ typedef struct kvc_params {
   int32_t agg_head;      /* kvc_agg over KV heads for I            (Section 3.3) */
   int32_t add_head_mean; /* 1: add the mean over KV heads to S (Section 3.2.2) */
   float softmax_scale;   /* 0 => 1/sqrt(d) (Preliminary eq. 3) */
+  /* ---- variants; 0 everywhere is the pass of Sections 3.2.2-3.3 ---- */
+  int32_t value_norm;    /* 1: A[q,m,c] is multiplied by ||V[l,h,c,:]||_2, h = q/G, before
+                            any aggregation (appendix on value norms, v-norm) */
+  int32_t order;         /* kvc_order of the output rows */
+  int32_t min_per_layer; /* m >= 0: ranks 0..min(m,N_b)-1 of every layer (of every head
+                            when unstructured) are kept first; only the other pool
+                            entries compete for the rest of the budget.  The paper
+                            defines no floor; this is the library's reading. */
+  int32_t unstructured;  /* 1: no head aggregation; the pool holds all Lyr*Hkv*N_b
+                            rank-aligned scores and every head keeps its own prefix
+                            (appendix on unstructured eviction) */
 } kvc_params;
 
 typedef struct kvc_inputs {
@@ -110,8 +137,9 @@ typedef struct kvc_inputs {
   const void* const* k;      /* host array [Lyr] of device pointers */
   const void* const* v;      /* host array [Lyr] of device pointers */
   const int64_t* cu_seqlens; /* host, [Bt+1] */
-  const int64_t* budget;     /* host, [Bt]: B_total of each sequence,
-                                0 <= budget[b] <= Lyr * N_b */
+  const int64_t* budget;     /* host, [Bt]: B_total of each sequence, in
+                                [R*min(min_per_layer, N_b), R*N_b] with R = Lyr
+                                (Lyr*Hkv when unstructured) */
 } kvc_inputs;
 
 typedef struct kvc_outputs {
@@ -151,10 +179,15 @@ kvc_status kvc_workspace_size(const kvc_params* params, int64_t total_tokens,
  *   S_task    = Agg_task over m;  S_group = Agg_group over q in [hG, hG+G);
  *   S[l,h,c]  = S_group[h,c] + (add_head_mean ? mean_i S_group[i,c] : 0).
  * bf16 inputs are multiplied on the matrix cores with fp32 accumulation; all
- * later arithmetic is fp32.  Writes S (device, float [Lyr,Hkv,T]). */
+ * later arithmetic is fp32.  Writes S (device, float [Lyr,Hkv,T]).
+ * v (host array [Lyr] of device pointers, layout of k) is read only when
+ * params->value_norm is set, and must then be given; else it may be NULL.  The
+ * weight ||V[l,h,c,:]|| does not depend on q or m, so it is applied to
+ * S_group[h,c] (it commutes with max and mean over m and over g). */
 kvc_status kvc_score(const kvc_params* params, const void* const* q,
-                     const void* const* k, const int64_t* cu_seqlens, float* S,
-                     void* workspace, size_t workspace_bytes, void* stream);
+                     const void* const* k, const void* const* v,
+                     const int64_t* cu_seqlens, float* S, void* workspace,
+                     size_t workspace_bytes, void* stream);
 
 /* Stage 2, Section 3.3 eq. 17 and the rank-aligned scores after it.  For each
  * (l,h) and sequence: idx = positions sorted by S descending, equal scores in
@@ -171,7 +204,11 @@ kvc_status kvc_composite(const kvc_params* params, const float* S_sorted,
 /* Stage 4, Section 3.3 pool / budget / N_l.  Per sequence: tau = budget-th
  * largest of the Lyr*N_b values I[l, seq tokens]; lengths = count of I > tau
  * plus, in ascending layer order, as many I == tau as still fit the budget.
- * offsets = exclusive prefix sum of lengths over (b,l).  tau may be NULL. */
+ * offsets = exclusive prefix sum of lengths over (b,l).  tau may be NULL.
+ * With min_per_layer = m the first min(m,N_b) ranks of each layer are counted
+ * in unconditionally and tau is the threshold of the competition for the rest
+ * (+inf if nothing is left to compete for).  With unstructured = 1, I is
+ * S_sorted (float [Lyr*Hkv, T]) and a "layer" above reads "(layer, head)". */
 kvc_status kvc_global_select(const kvc_params* params, const float* I,
                              const int64_t* cu_seqlens, const int64_t* budget,
                              float* tau, int32_t* lengths, int64_t* offsets,
@@ -180,14 +217,19 @@ kvc_status kvc_global_select(const kvc_params* params, const float* I,
 /* Stage 5, Section 3.3 final selection.  Copies rows idx[l,h,0..N_{b,l}) of
  * K and V (bit copies) into the pools; lengths/offsets are read on the device.
  * total_budget = sum_b budget[b] (host value, sizes the launch).  v and v_out
- * may both be NULL to gather keys only. */
+ * may both be NULL to gather keys only.  KVC_ORDER_POSITION first turns every
+ * retained prefix idx[l,h,0..N) into its ascending permutation (a bit mask per
+ * head and a prefix sum over it) and needs workspace (kvc_workspace_size
+ * covers it); with KVC_ORDER_RANK workspace may be NULL. */
 kvc_status kvc_gather(const kvc_params* params, const void* const* k,
                       const void* const* v, const int32_t* idx,
                       const int32_t* lengths, const int64_t* offsets,
                       const int64_t* cu_seqlens, int64_t total_budget, void* k_out,
-                      void* v_out, void* stream);
+                      void* v_out, void* workspace, size_t workspace_bytes,
+                      void* stream);
 
-/* The whole pass: stages 1-5 on one stream, no host synchronisation. */
+/* The whole pass: stages 1-5 on one stream, no host synchronisation.  With
+ * unstructured = 1 stage 3 is skipped and out->composite is not written. */
 kvc_status kvc_compress(const kvc_params* params, const kvc_inputs* in,
                         const kvc_outputs* out, void* workspace,
                         size_t workspace_bytes, void* stream);

@@ -14,6 +14,7 @@ from typing import Optional, Sequence
 
 KVC_F32, KVC_BF16 = 0, 1
 KVC_AGG_MAX, KVC_AGG_MEAN = 0, 1
+KVC_ORDER_RANK, KVC_ORDER_POSITION = 0, 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
@@ -35,13 +36,17 @@ class KvcParams(C.Structure):
         ("head_dim", C.c_int32), ("window", C.c_int32), ("dtype", C.c_int32),
         ("agg_task", C.c_int32), ("agg_group", C.c_int32), ("agg_head", C.c_int32),
         ("add_head_mean", C.c_int32), ("softmax_scale", C.c_float),
+        ("value_norm", C.c_int32), ("order", C.c_int32), ("min_per_layer", C.c_int32),
+        ("unstructured", C.c_int32),
     ]
 
     def __init__(self, batch, layers, hq, hkv, head_dim, window, dtype, agg_task=KVC_AGG_MAX,
                  agg_group=KVC_AGG_MEAN, agg_head=KVC_AGG_MEAN, add_head_mean=1,
-                 softmax_scale=0.0):
+                 softmax_scale=0.0, value_norm=0, order=KVC_ORDER_RANK, min_per_layer=0,
+                 unstructured=0):
         super().__init__(batch, layers, hq, hkv, head_dim, window, dtype, agg_task, agg_group,
-                         agg_head, add_head_mean, softmax_scale)
+                         agg_head, add_head_mean, softmax_scale, value_norm, order,
+                         min_per_layer, unstructured)
 
 
 class _Inputs(C.Structure):
@@ -74,11 +79,12 @@ def lib() -> C.CDLL:
         pp, vp, i64p = C.POINTER(KvcParams), C.c_void_p, C.POINTER(C.c_int64)
         ptab = C.POINTER(C.c_void_p)
         L.kvc_workspace_size.argtypes = [pp, C.c_int64, C.c_int64, C.POINTER(C.c_size_t)]
-        L.kvc_score.argtypes = [pp, ptab, ptab, i64p, vp, vp, C.c_size_t, vp]
+        L.kvc_score.argtypes = [pp, ptab, ptab, ptab, i64p, vp, vp, C.c_size_t, vp]
         L.kvc_head_rank.argtypes = [pp, vp, i64p, vp, vp, vp, C.c_size_t, vp]
         L.kvc_composite.argtypes = [pp, vp, i64p, vp, vp]
         L.kvc_global_select.argtypes = [pp, vp, i64p, i64p, vp, vp, vp, vp, C.c_size_t, vp]
-        L.kvc_gather.argtypes = [pp, ptab, ptab, vp, vp, vp, i64p, C.c_int64, vp, vp, vp]
+        L.kvc_gather.argtypes = [pp, ptab, ptab, vp, vp, vp, i64p, C.c_int64, vp, vp, vp,
+                                 C.c_size_t, vp]
         L.kvc_compress.argtypes = [pp, C.POINTER(_Inputs), C.POINTER(_Outputs), vp, C.c_size_t, vp]
         for name in ("kvc_workspace_size", "kvc_score", "kvc_head_rank", "kvc_composite",
                      "kvc_global_select", "kvc_gather", "kvc_compress"):
@@ -134,9 +140,10 @@ def kvc_workspace_size(params: KvcParams, total_tokens: int, max_seqlen: int) ->
     return out.value
 
 
-def kvc_score(params, q, k, cu_seqlens, S, workspace, workspace_bytes, stream=0):
-    _check(lib().kvc_score(C.byref(params), _ptr_table(q), _ptr_table(k), _i64(cu_seqlens),
-                           _vp(S), _vp(workspace), workspace_bytes, _vp(stream)), "kvc_score")
+def kvc_score(params, q, k, cu_seqlens, S, workspace, workspace_bytes, stream=0, v=None):
+    _check(lib().kvc_score(C.byref(params), _ptr_table(q), _ptr_table(k), _ptr_table(v),
+                           _i64(cu_seqlens), _vp(S), _vp(workspace), workspace_bytes,
+                           _vp(stream)), "kvc_score")
 
 
 def kvc_head_rank(params, S, cu_seqlens, idx, S_sorted, workspace, workspace_bytes, stream=0):
@@ -158,10 +165,11 @@ def kvc_global_select(params, I, cu_seqlens, budget, tau, lengths, offsets, work
 
 
 def kvc_gather(params, k, v, idx, lengths, offsets, cu_seqlens, total_budget, k_out, v_out,
-               stream=0):
+               stream=0, workspace=0, workspace_bytes=0):
     _check(lib().kvc_gather(C.byref(params), _ptr_table(k), _ptr_table(v), _vp(idx),
                             _vp(lengths), _vp(offsets), _i64(cu_seqlens), total_budget,
-                            _vp(k_out), _vp(v_out), _vp(stream)), "kvc_gather")
+                            _vp(k_out), _vp(v_out), _vp(workspace), workspace_bytes,
+                            _vp(stream)), "kvc_gather")
 
 
 def kvc_compress(params, q, k, v, cu_seqlens, budget, k_out, v_out, lengths, offsets,

@@ -66,6 +66,13 @@ static kvc_status check_params(const kvc_params* p) {
   if (!(p->softmax_scale >= 0.0f) || !std::isfinite(p->softmax_scale)) {
     set_error("softmax_scale must be finite and >= 0"); return KVC_ERR_INVALID_ARG;
   }
+  if ((p->value_norm | p->unstructured) & ~1) {
+    set_error("value_norm and unstructured must be 0 or 1"); return KVC_ERR_INVALID_ARG;
+  }
+  if (p->order != KVC_ORDER_RANK && p->order != KVC_ORDER_POSITION) {
+    set_error("unknown output order %d", p->order); return KVC_ERR_INVALID_ARG;
+  }
+  if (p->min_per_layer < 0) { set_error("min_per_layer must be >= 0"); return KVC_ERR_INVALID_ARG; }
   if (p->batch > KVC_MAX_BATCH) {
     set_error("batch %d exceeds KVC_MAX_BATCH", p->batch); return KVC_ERR_UNSUPPORTED;
   }
@@ -79,6 +86,9 @@ static kvc_status check_params(const kvc_params* p) {
   }
   if (p->window > 4096 || p->hq > 1024) {
     set_error("window > 4096 or hq > 1024 unsupported"); return KVC_ERR_UNSUPPORTED;
+  }
+  if (int64_t(p->layers) * p->hkv > 65535) {
+    set_error("layers * hkv > 65535 unsupported"); return KVC_ERR_UNSUPPORTED;
   }
   return KVC_OK;
 }
@@ -101,6 +111,9 @@ static kvc_status make_problem(const kvc_params* p, const int64_t* cu, Problem* 
   pb->group = p->hq / p->hkv; pb->d = p->head_dim; pb->window = p->window;
   pb->dtype = p->dtype; pb->agg_task = p->agg_task; pb->agg_group = p->agg_group;
   pb->agg_head = p->agg_head; pb->add_head_mean = p->add_head_mean;
+  pb->value_norm = p->value_norm; pb->order = p->order; pb->min_per_layer = p->min_per_layer;
+  pb->unstructured = p->unstructured;
+  pb->sel_rows = p->unstructured ? p->layers * p->hkv : p->layers;
   pb->scale = p->softmax_scale > 0.0f ? p->softmax_scale
                                       : 1.0f / std::sqrt(float(p->head_dim));
   pb->total = cu[p->batch];
@@ -136,9 +149,11 @@ static kvc_status check_budget(const Problem& pb, const int64_t* cu, const int64
   int64_t sum = 0;
   for (int b = 0; b < pb.batch; ++b) {
     int64_t n = cu[b + 1] - cu[b];
-    if (budget[b] < 0 || budget[b] > int64_t(pb.layers) * n) {
-      set_error("budget[%d]=%lld outside [0, layers*N_b=%lld]", b, (long long)budget[b],
-                (long long)(int64_t(pb.layers) * n));
+    const int64_t floor_b = pb.min_per_layer < n ? pb.min_per_layer : n;
+    if (budget[b] < int64_t(pb.sel_rows) * floor_b || budget[b] > int64_t(pb.sel_rows) * n) {
+      set_error("budget[%d]=%lld outside [rows*min(min_per_layer,N_b)=%lld, rows*N_b=%lld]", b,
+                (long long)budget[b], (long long)(int64_t(pb.sel_rows) * floor_b),
+                (long long)(int64_t(pb.sel_rows) * n));
       return KVC_ERR_INVALID_ARG;
     }
     sum += budget[b];
@@ -168,6 +183,8 @@ static CompressLayout compress_layout(const Problem& pb) {
   if (r > stage) stage = r;
   size_t s = select_workspace_bytes(pb);
   if (s > stage) stage = s;
+  size_t g = gather_workspace_bytes(pb);
+  if (g > stage) stage = g;
   cur += align_up(stage);
   L.total = cur;
   return L;
@@ -252,17 +269,19 @@ kvc_status kvc_workspace_size(const kvc_params* params, int64_t total_tokens,
 }
 
 kvc_status kvc_score(const kvc_params* params, const void* const* q, const void* const* k,
-                     const int64_t* cu_seqlens, float* S, void* workspace,
+                     const void* const* v, const int64_t* cu_seqlens, float* S, void* workspace,
                      size_t workspace_bytes, void* stream) {
   Problem pb{};
   kvc_status st = make_problem(params, cu_seqlens, &pb);
   if (st != KVC_OK) return st;
   if ((st = check_ptr_table(q, pb.layers, "q")) != KVC_OK) return st;
   if ((st = check_ptr_table(k, pb.layers, "k")) != KVC_OK) return st;
+  if (pb.value_norm && (st = check_ptr_table(v, pb.layers, "v")) != KVC_OK) return st;
   if (!S) { set_error("S is NULL"); return KVC_ERR_INVALID_ARG; }
   if ((st = check_ws(workspace, workspace_bytes, score_workspace_bytes(pb))) != KVC_OK) return st;
   if (pb.total == 0) return KVC_OK;
-  return launch_score(pb, q, k, S, workspace, static_cast<hipStream_t>(stream));
+  return launch_score(pb, q, k, pb.value_norm ? v : nullptr, S, workspace,
+                      static_cast<hipStream_t>(stream));
 }
 
 kvc_status kvc_head_rank(const kvc_params* params, const float* S, const int64_t* cu_seqlens,
@@ -305,7 +324,7 @@ kvc_status kvc_global_select(const kvc_params* params, const float* I,
 kvc_status kvc_gather(const kvc_params* params, const void* const* k, const void* const* v,
                       const int32_t* idx, const int32_t* lengths, const int64_t* offsets,
                       const int64_t* cu_seqlens, int64_t total_budget, void* k_out, void* v_out,
-                      void* stream) {
+                      void* workspace, size_t workspace_bytes, void* stream) {
   Problem pb{};
   kvc_status st = make_problem(params, cu_seqlens, &pb);
   if (st != KVC_OK) return st;
@@ -317,12 +336,13 @@ kvc_status kvc_gather(const kvc_params* params, const void* const* k, const void
   if (!idx || !lengths || !offsets) {
     set_error("idx, lengths or offsets is NULL"); return KVC_ERR_INVALID_ARG;
   }
-  if (total_budget < 0 || total_budget > int64_t(pb.layers) * pb.total) {
-    set_error("total_budget outside [0, layers*T]"); return KVC_ERR_INVALID_ARG;
+  if (total_budget < 0 || total_budget > int64_t(pb.sel_rows) * pb.total) {
+    set_error("total_budget outside [0, rows*T]"); return KVC_ERR_INVALID_ARG;
   }
+  if ((st = check_ws(workspace, workspace_bytes, gather_workspace_bytes(pb))) != KVC_OK) return st;
   if (total_budget == 0) return KVC_OK;
   if (!k_out) { set_error("k_out is NULL"); return KVC_ERR_INVALID_ARG; }
-  return launch_gather(pb, k, v, idx, lengths, offsets, total_budget, k_out, v_out,
+  return launch_gather(pb, k, v, idx, lengths, offsets, total_budget, k_out, v_out, workspace,
                        static_cast<hipStream_t>(stream));
 }
 
@@ -346,6 +366,7 @@ kvc_status kvc_compress(const kvc_params* params, const kvc_inputs* in, const kv
     set_error("v and v_out must both be given or both be NULL"); return KVC_ERR_INVALID_ARG;
   }
   if (in->v && (st = check_ptr_table(in->v, pb.layers, "v")) != KVC_OK) return st;
+  if (pb.value_norm && !in->v) { set_error("value_norm needs v"); return KVC_ERR_INVALID_ARG; }
   int64_t total_budget = 0;
   if ((st = check_budget(pb, in->cu_seqlens, in->budget, &total_budget)) != KVC_OK) return st;
   if (!out->lengths || !out->offsets) {
@@ -365,16 +386,19 @@ kvc_status kvc_compress(const kvc_params* params, const kvc_inputs* in, const kv
   hipStream_t s = static_cast<hipStream_t>(stream);
 
   if (pb.total > 0) {
-    if ((st = launch_score(pb, in->q, in->k, S, stage, s)) != KVC_OK) return st;
+    if ((st = launch_score(pb, in->q, in->k, pb.value_norm ? in->v : nullptr, S, stage, s)) !=
+        KVC_OK)
+      return st;
     if ((st = launch_head_rank(pb, S, idx, sorted, stage, s)) != KVC_OK) return st;
-    if ((st = launch_composite(pb, sorted, I, s)) != KVC_OK) return st;
+    if (!pb.unstructured && (st = launch_composite(pb, sorted, I, s)) != KVC_OK) return st;
   }
-  if ((st = launch_global_select(pb, I, in->budget, tau, out->lengths, out->offsets, stage, s)) !=
-      KVC_OK)
+  // unstructured: the pool is the rank-aligned per-head scores themselves
+  if ((st = launch_global_select(pb, pb.unstructured ? sorted : I, in->budget, tau, out->lengths,
+                                 out->offsets, stage, s)) != KVC_OK)
     return st;
   if (total_budget > 0) {
     st = launch_gather(pb, in->k, in->v, idx, out->lengths, out->offsets, total_budget,
-                       out->k_out, out->v_out, s);
+                       out->k_out, out->v_out, stage, s);
   }
   return st;
 }

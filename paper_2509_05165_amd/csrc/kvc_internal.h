@@ -22,6 +22,8 @@ struct PtrTable {
 struct Problem {
   int32_t batch, layers, hq, hkv, group, d, window, dtype;
   int32_t agg_task, agg_group, agg_head, add_head_mean;
+  int32_t value_norm, order, min_per_layer, unstructured;
+  int32_t sel_rows;   // rows of the selection pool per sequence: layers, or layers*hkv
   float scale;        // softmax scale actually used
   int64_t total;      // T
   int64_t max_seqlen;
@@ -56,7 +58,7 @@ void prof_end(hipStream_t stream);
 // ---------------------------------------------------------------------------
 size_t score_workspace_bytes(const Problem& pb);
 kvc_status launch_score(const Problem& pb, const void* const* q, const void* const* k,
-                        float* S, void* ws, hipStream_t stream);
+                        const void* const* v, float* S, void* ws, hipStream_t stream);
 
 size_t rank_workspace_bytes(const Problem& pb);
 kvc_status launch_head_rank(const Problem& pb, const float* S, int32_t* idx, float* S_sorted,
@@ -70,9 +72,11 @@ kvc_status launch_global_select(const Problem& pb, const float* I, const int64_t
                                 float* tau, int32_t* lengths, int64_t* offsets, void* ws,
                                 hipStream_t stream);
 
+size_t gather_workspace_bytes(const Problem& pb);
 kvc_status launch_gather(const Problem& pb, const void* const* k, const void* const* v,
                          const int32_t* idx, const int32_t* lengths, const int64_t* offsets,
-                         int64_t total_budget, void* k_out, void* v_out, hipStream_t stream);
+                         int64_t total_budget, void* k_out, void* v_out, void* ws,
+                         hipStream_t stream);
 
 kvc_status launch_copy_probe(void* dst, const void* src, size_t bytes, hipStream_t stream);
 

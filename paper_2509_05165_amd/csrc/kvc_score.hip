@@ -219,10 +219,15 @@ __global__ __launch_bounds__(256) void score_merge(SeqTable seq, int rows_per_se
 // One thread per token; in place when part == S and row_chunks == 1.  blockIdx.y
 // is a layer: both pointers advance by layer_stride floats per layer (one launch
 // can finish all layers when they were emitted in place).
+//
+// vnorm (may be null): [hkv, total] weights ||V[h,c,:]|| of this layer; the
+// weighted attention matrix of the value-norm appendix scales every entry of
+// column c of head h by the same non-negative number, which commutes with the
+// max / mean over task tokens and over the group, so it is applied here.
 // ---------------------------------------------------------------------------
 __global__ void score_finish(const float* part, int row_chunks, int hkv, int total,
                              float group_norm, int group_max, int add_head_mean, float* S,
-                             size_t layer_stride) {
+                             size_t layer_stride, const float* __restrict__ vnorm) {
   const int c = blockIdx.x * blockDim.x + threadIdx.x;
   if (c >= total) return;
   part += blockIdx.y * layer_stride;
@@ -238,6 +243,7 @@ __global__ void score_finish(const float* part, int row_chunks, int hkv, int tot
         v = group_max ? fmaxf(v, x) : v + x;
       }
       v *= group_norm;
+      if (vnorm) v *= vnorm[(size_t)(h0 + i) * total + c];
       vals[i] = v;
       sum += v;
     }
@@ -256,8 +262,47 @@ __global__ void score_finish(const float* part, int row_chunks, int hkv, int tot
       const float x = part[((size_t)rc * hkv + h) * total + c];
       v = group_max ? fmaxf(v, x) : v + x;
     }
-    S[(size_t)h * total + c] = v * group_norm + mean;
+    v *= group_norm;
+    if (vnorm) v *= vnorm[(size_t)h * total + c];
+    S[(size_t)h * total + c] = v + mean;
   }
+}
+
+// ---------------------------------------------------------------------------
+// value norms of one layer: w[h, c] = ||V[h, c, :]||_2 in fp32.  A group of
+// 16 lanes squares and sums one row (16 bytes per lane and step), four rows
+// per wave instruction.
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void value_norm_kernel(const T* __restrict__ v, size_t rows,
+                                                         int d, float* __restrict__ w) {
+  constexpr int PER = 16 / sizeof(T);          // elements per 16-byte piece
+  const int sub = threadIdx.x & 15;
+  const size_t row = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) >> 4;
+  float acc = 0.f;
+  if (row < rows) {
+    const T* p = v + row * d;
+    for (int j = sub * PER; j < d; j += 16 * PER) {
+      const uint4 raw = *reinterpret_cast<const uint4*>(p + j);
+      if (sizeof(T) == 2) {
+        const uint32_t u[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float lo = __uint_as_float(u[i] << 16), hi = __uint_as_float(u[i] & 0xffff0000u);
+          acc = fmaf(lo, lo, acc);
+          acc = fmaf(hi, hi, acc);
+        }
+      } else {
+        const float f[4] = {__uint_as_float(raw.x), __uint_as_float(raw.y), __uint_as_float(raw.z),
+                            __uint_as_float(raw.w)};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc = fmaf(f[i], f[i], acc);
+      }
+    }
+  }
+#pragma unroll
+  for (int off = 8; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
+  if (row < rows && sub == 0) w[row] = sqrtf(acc);
 }
 
 
@@ -266,7 +311,7 @@ constexpr int MF_CHUNK = 2048;
 constexpr int MIN_CHUNK = 256;   // workspace is sized for the smallest chunk in use
 
 struct ScoreLayout {
-  size_t off_m, off_s, off_lse, off_part, total;
+  size_t off_m, off_s, off_lse, off_part, off_vnorm, total;
   int max_chunks, rows_layer, row_chunks;
 };
 
@@ -285,6 +330,8 @@ ScoreLayout score_layout(const Problem& pb) {
   // KV heads make the in-place finish impossible
   if (L.row_chunks > 1 || pb.hkv > 8)
     cur += align_up(size_t(L.row_chunks) * pb.hkv * size_t(pb.total) * 4);
+  L.off_vnorm = cur;
+  if (pb.value_norm) cur += align_up(size_t(pb.hkv) * size_t(pb.total) * 4);   // one layer's weights
   L.total = cur;
   return L;
 }
@@ -293,14 +340,16 @@ ScoreLayout score_layout(const Problem& pb) {
 
 size_t score_workspace_bytes(const Problem& pb) { return score_layout(pb).total; }
 
-kvc_status launch_score(const Problem& pb, const void* const* q, const void* const* k, float* S,
-                        void* ws, hipStream_t stream) {
+kvc_status launch_score(const Problem& pb, const void* const* q, const void* const* k,
+                        const void* const* v, float* S, void* ws, hipStream_t stream) {
   const ScoreLayout L = score_layout(pb);
   char* w = static_cast<char*>(ws);
   float* part_m = reinterpret_cast<float*>(w + L.off_m);
   float* part_s = reinterpret_cast<float*>(w + L.off_s);
   float* lse2 = reinterpret_cast<float*>(w + L.off_lse);
   const bool separate = L.row_chunks > 1 || pb.hkv > 8;
+  float* vnorm = v ? reinterpret_cast<float*>(w + L.off_vnorm) : nullptr;
+  const bool per_layer_finish = separate || vnorm != nullptr;
   const float c2 = pb.scale * LOG2E;
   const int total = int(pb.total);
   const int task_max = pb.agg_task == KVC_AGG_MAX, group_max = pb.agg_group == KVC_AGG_MAX;
@@ -367,15 +416,26 @@ kvc_status launch_score(const Problem& pb, const void* const* q, const void* con
             group_max, part));
       }
     }
-    // with separate partials each layer is finished before the next one reuses them
-    if (separate)
+    // with separate partials (or one buffer of value norms) each layer is finished
+    // before the next one reuses them
+    if (vnorm) {
+      const size_t rows = size_t(pb.hkv) * total;
+      const unsigned blocks = unsigned((rows * 16 + 255) / 256);
+      if (pb.dtype == KVC_BF16)
+        KVC_LAUNCH("value_norm_kernel", stream, value_norm_kernel<uint16_t><<<blocks, 256, 0, stream>>>(
+            static_cast<const uint16_t*>(v[l]), rows, pb.d, vnorm));
+      else
+        KVC_LAUNCH("value_norm_kernel", stream, value_norm_kernel<float><<<blocks, 256, 0, stream>>>(
+            static_cast<const float*>(v[l]), rows, pb.d, vnorm));
+    }
+    if (per_layer_finish)
       KVC_LAUNCH("score_finish", stream, score_finish<<<(total + 255) / 256, 256, 0, stream>>>(
-          part, L.row_chunks, pb.hkv, total, group_norm, group_max, pb.add_head_mean, S_l, 0));
+          part, L.row_chunks, pb.hkv, total, group_norm, group_max, pb.add_head_mean, S_l, 0, vnorm));
   }
   // emitted in place: one launch finishes every layer
-  if (!separate && pb.layers > 0 && total > 0)
+  if (!per_layer_finish && pb.layers > 0 && total > 0)
     KVC_LAUNCH("score_finish", stream, score_finish<<<dim3((total + 255) / 256, pb.layers), 256, 0, stream>>>(
-        S, 1, pb.hkv, total, group_norm, group_max, pb.add_head_mean, S, size_t(pb.hkv) * total));
+        S, 1, pb.hkv, total, group_norm, group_max, pb.add_head_mean, S, size_t(pb.hkv) * total, nullptr));
   return KVC_OK;
 }
 

@@ -9,6 +9,11 @@
 // above the threshold and those equal to it; ties are granted in ascending
 // layer order until the budget is met (within a layer the tied entries are the
 // ranks right after the ones above the threshold, so each layer keeps a prefix).
+//
+// A "layer" here is a row of the pool: a layer, or a (layer, head) pair in the
+// unstructured variant.  With a per-row floor f the first f ranks of every row
+// are kept unconditionally and stay out of the histograms; the budget that is
+// searched for is what remains after them.
 #include "kvc_internal.h"
 
 namespace kvc {
@@ -34,6 +39,7 @@ __device__ __forceinline__ void digit_of(int pass, uint32_t key, uint32_t* digit
   else { *digit = key & 1023u; *hi = key >> 10; }
 }
 
+// budget.b[] already excludes the floor entries
 __global__ void select_init(uint32_t* hist, int count, SelState* state, BudgetTable budget,
                             int batch) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -43,14 +49,14 @@ __global__ void select_init(uint32_t* hist, int count, SelState* state, BudgetTa
 
 // grid: (token blocks, layers, batch)
 __global__ __launch_bounds__(SEL_THREADS) void select_hist(
-    const float* __restrict__ I, SeqTable seq, int total, int pass,
+    const float* __restrict__ I, SeqTable seq, int total, int pass, int floor_rank,
     const SelState* __restrict__ state, uint32_t* __restrict__ hist /* [batch][3][SEL_BINS] */) {
   __shared__ uint32_t lh[SEL_BINS];
   const int b = blockIdx.z;
   const int tok0 = seq.cu[b], n = seq.cu[b + 1] - tok0;
-  const int begin = blockIdx.x * SEL_PER_BLOCK;
-  if (begin >= n) return;
-  const int end = min(n, begin + SEL_PER_BLOCK);
+  const int begin = max(blockIdx.x * SEL_PER_BLOCK, floor_rank);   // ranks below the floor do not compete
+  if (begin >= n || begin >= (int)(blockIdx.x + 1) * SEL_PER_BLOCK) return;
+  const int end = min(n, (int)(blockIdx.x + 1) * SEL_PER_BLOCK);
   for (int i = threadIdx.x; i < SEL_BINS; i += SEL_THREADS) lh[i] = 0;
   __syncthreads();
   const uint32_t want_hi = pass == 0 ? 0u : (pass == 1 ? state[b].prefix >> 21 : state[b].prefix >> 10);
@@ -106,14 +112,14 @@ __global__ __launch_bounds__(SEL_THREADS) void select_find(int pass, const uint3
 
 // grid: (token blocks, layers, batch): counts[b][l] = {#(I > tau), #(I == tau)}
 __global__ __launch_bounds__(SEL_THREADS) void select_count(
-    const float* __restrict__ I, SeqTable seq, int total, int layers,
+    const float* __restrict__ I, SeqTable seq, int total, int layers, int floor_rank,
     const SelState* __restrict__ state, uint32_t* __restrict__ counts) {
   __shared__ uint32_t sh[2];
   const int b = blockIdx.z;
   const int tok0 = seq.cu[b], n = seq.cu[b + 1] - tok0;
-  const int begin = blockIdx.x * SEL_PER_BLOCK;
-  if (begin >= n) return;
-  const int end = min(n, begin + SEL_PER_BLOCK);
+  const int begin = max(blockIdx.x * SEL_PER_BLOCK, floor_rank);
+  if (begin >= n || begin >= (int)(blockIdx.x + 1) * SEL_PER_BLOCK) return;
+  const int end = min(n, (int)(blockIdx.x + 1) * SEL_PER_BLOCK);
   if (threadIdx.x < 2) sh[threadIdx.x] = 0;
   __syncthreads();
   const uint32_t tau = state[b].prefix;
@@ -132,7 +138,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_count(
 }
 
 // one thread: lengths, offsets, tau
-__global__ void select_finalize(SeqTable seq, int layers, BudgetTable budget,
+__global__ void select_finalize(SeqTable seq, int layers, int floor_rank, BudgetTable budget,
                                 const SelState* __restrict__ state,
                                 const uint32_t* __restrict__ counts, float* tau,
                                 int32_t* lengths, int64_t* offsets) {
@@ -140,18 +146,20 @@ __global__ void select_finalize(SeqTable seq, int layers, BudgetTable budget,
   int64_t off = 0;
   for (int b = 0; b < seq.batch; ++b) {
     const int64_t want = budget.b[b];
+    const int n_b = seq.cu[b + 1] - seq.cu[b];
+    const int64_t kept_first = floor_rank < n_b ? floor_rank : n_b;   // the floor entries
     if (tau) tau[b] = want > 0 ? ordered_to_float(state[b].prefix) : __builtin_inff();
     int64_t above = 0;
     for (int l = 0; l < layers; ++l) above += counts[((size_t)b * layers + l) * 2];
     int64_t ties_left = want - above;
     for (int l = 0; l < layers; ++l) {
-      int64_t len = 0;
+      int64_t len = kept_first;
       if (want > 0) {
         const int64_t gt = counts[((size_t)b * layers + l) * 2];
         const int64_t eq = counts[((size_t)b * layers + l) * 2 + 1];
         const int64_t take = eq < ties_left ? eq : ties_left;
         ties_left -= take;
-        len = gt + take;
+        len += gt + take;
       }
       lengths[b * layers + l] = (int32_t)len;
       offsets[b * layers + l] = off;
@@ -167,7 +175,7 @@ SelectLayout select_layout(const Problem& pb) {
   SelectLayout L{};
   size_t cur = 0;
   const size_t hist_words = size_t(pb.batch) * 3 * SEL_BINS;
-  const size_t count_words = size_t(pb.batch) * pb.layers * 2;
+  const size_t count_words = size_t(pb.batch) * pb.sel_rows * 2;
   L.off_hist = cur;   cur += hist_words * 4;
   L.off_counts = cur; cur += align_up(count_words * 4);
   L.words = int((cur) / 4);                   // hist and counts are zeroed together
@@ -188,21 +196,25 @@ kvc_status launch_global_select(const Problem& pb, const float* I, const int64_t
   uint32_t* hist = reinterpret_cast<uint32_t*>(w + L.off_hist);
   uint32_t* counts = reinterpret_cast<uint32_t*>(w + L.off_counts);
   SelState* state = reinterpret_cast<SelState*>(w + L.off_state);
-  BudgetTable bt{};
-  for (int b = 0; b < pb.batch; ++b) bt.b[b] = budget[b];
+  const int rows = pb.sel_rows, floor_rank = pb.min_per_layer;
+  BudgetTable bt{};   // what is left to compete for after the floor entries
+  for (int b = 0; b < pb.batch; ++b) {
+    const int64_t n_b = pb.seq.cu[b + 1] - pb.seq.cu[b];
+    bt.b[b] = budget[b] - int64_t(rows) * (floor_rank < n_b ? floor_rank : n_b);
+  }
   const int total = int(pb.total);
 
   KVC_LAUNCH("select_init", stream, select_init<<<(L.words + 255) / 256, 256, 0, stream>>>(hist, L.words, state, bt, pb.batch));
   if (pb.max_seqlen > 0) {
-    dim3 grid((unsigned)((pb.max_seqlen + SEL_PER_BLOCK - 1) / SEL_PER_BLOCK), pb.layers, pb.batch);
+    dim3 grid((unsigned)((pb.max_seqlen + SEL_PER_BLOCK - 1) / SEL_PER_BLOCK), rows, pb.batch);
     for (int pass = 0; pass < 3; ++pass) {
-      KVC_LAUNCH("select_hist", stream, select_hist<<<grid, SEL_THREADS, 0, stream>>>(I, pb.seq, total, pass, state, hist));
+      KVC_LAUNCH("select_hist", stream, select_hist<<<grid, SEL_THREADS, 0, stream>>>(I, pb.seq, total, pass, floor_rank, state, hist));
       KVC_LAUNCH("select_find", stream, select_find<<<pb.batch, SEL_THREADS, 0, stream>>>(pass, hist, state));
     }
-    KVC_LAUNCH("select_count", stream, select_count<<<grid, SEL_THREADS, 0, stream>>>(I, pb.seq, total, pb.layers, state, counts));
+    KVC_LAUNCH("select_count", stream, select_count<<<grid, SEL_THREADS, 0, stream>>>(I, pb.seq, total, rows, floor_rank, state, counts));
   }
-  KVC_LAUNCH("select_finalize", stream, select_finalize<<<1, 64, 0, stream>>>(pb.seq, pb.layers, bt, state, counts, tau, lengths,
-                                        offsets));
+  KVC_LAUNCH("select_finalize", stream, select_finalize<<<1, 64, 0, stream>>>(pb.seq, rows, floor_rank, bt, state, counts, tau,
+                                        lengths, offsets));
   return KVC_OK;
 }
 

@@ -129,3 +129,27 @@ def test_empty_problem_is_a_no_op_without_gpu():
     kv.kvc_head_rank(p, FAKE, [0, 0], FAKE, FAKE, FAKE, 1 << 20)
     kv.kvc_composite(p, FAKE, [0, 0], FAKE)
     kv.kvc_gather(p, [FAKE] * 2, [FAKE] * 2, FAKE, FAKE, FAKE, [0, 0], 0, FAKE, FAKE)
+
+
+def test_variant_parameter_checks():
+    expect(1, kv.kvc_workspace_size, P(value_norm=2), 100, 100)
+    expect(1, kv.kvc_workspace_size, P(order=2), 100, 100)
+    expect(1, kv.kvc_workspace_size, P(min_per_layer=-1), 100, 100)
+    expect(1, kv.kvc_workspace_size, P(unstructured=3), 100, 100)
+    # the variants never need less workspace than the plain pass
+    base = kv.kvc_workspace_size(P(), 50000, 50000)
+    assert kv.kvc_workspace_size(P(value_norm=1), 50000, 50000) >= base
+    assert kv.kvc_workspace_size(P(order=kv.KVC_ORDER_POSITION), 50000, 50000) >= base
+
+
+def test_variant_argument_checks_run_before_any_gpu_call():
+    cu = [0, 100]
+    # value norms need the value pointers
+    expect(1, kv.kvc_score, P(value_norm=1), [FAKE] * 2, [FAKE] * 2, cu, FAKE, FAKE, 1 << 30)
+    # a budget below layers * floor cannot be met
+    expect(1, kv.kvc_global_select, P(min_per_layer=10), FAKE, cu, [19], 0, FAKE, FAKE, FAKE, 1 << 30)
+    # unstructured: the budget counts (head, token) entries, up to layers*hkv*N
+    expect(1, kv.kvc_global_select, P(unstructured=1), FAKE, cu, [2 * 4 * 100 + 1], 0, FAKE, FAKE, FAKE, 1 << 30)
+    # position order needs workspace in the gather stage
+    expect(3, kv.kvc_gather, P(order=kv.KVC_ORDER_POSITION), [FAKE] * 2, [FAKE] * 2, FAKE, FAKE, FAKE,
+           cu, 5, FAKE, FAKE, 0)
