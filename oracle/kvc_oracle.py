@@ -41,6 +41,11 @@ Variants beyond the default pass (each off unless asked for):
 * per-layer floor m (the paper does not exclude N_l = 0 and defines no floor;
   this reading): ranks 0..m-1 of every layer are taken first, the rest of the
   budget goes to the top of the remaining pool with the usual tie rule.
+* causal tail (a reading for the case where the M task tokens are the last M
+  tokens of the context itself, the task-agnostic setting of Section 3.2.1):
+  task token m sits at position N-M+m and attends to the cached keys at
+  positions <= N-M+m only; its softmax runs over those keys and the other
+  entries of its row of A are 0.  Needs N >= M.
 * unstructured selection (Appendix on unstructured eviction): the head
   aggregation is skipped, the pool holds all Lyr*Hkv*N rank-aligned scores,
   the budget counts (head, token) entries and every head keeps its own prefix
@@ -81,20 +86,27 @@ def _agg(x: np.ndarray, op: int, axis: int) -> np.ndarray:
 # --------------------------------------------------------------------------
 # Section 3.2.2: attention collection and aggregation
 # --------------------------------------------------------------------------
-def attention(q_rows: np.ndarray, keys: np.ndarray, scale: float) -> np.ndarray:
+def attention(q_rows: np.ndarray, keys: np.ndarray, scale: float,
+              causal_tail: bool = False) -> np.ndarray:
     """A[m, c] = softmax_c(q_m . k_c * scale) for M query rows and N cached keys.
 
     Preliminary eq. 3 applied to each task token; the softmax runs over the N
-    cached keys only.
+    cached keys only.  causal_tail: row m only sees keys c <= N - M + m.
     """
     s = (q_rows @ keys.T) * scale                     # [M, N]
+    if causal_tail:
+        m, n = s.shape
+        if n < m:
+            raise ValueError("causal tail needs N >= M")
+        hidden = np.arange(n)[None, :] > (n - m + np.arange(m))[:, None]
+        s = np.where(hidden, -np.inf, s)
     s = s - s.max(axis=1, keepdims=True)
     e = np.exp(s)
     return e / e.sum(axis=1, keepdims=True)
 
 
 def score_layer(q, k, *, agg_task=AGG_MAX, agg_group=AGG_MEAN, add_head_mean=True,
-                scale=None, v=None) -> np.ndarray:
+                scale=None, v=None, causal_tail=False) -> np.ndarray:
     """S[h, c] for one layer of one sequence.
 
     q: [Hq, M, d], k: [Hkv, N, d] (float64).  Follows, in order, the three
@@ -114,7 +126,7 @@ def score_layer(q, k, *, agg_task=AGG_MAX, agg_group=AGG_MEAN, add_head_mean=Tru
         scale = 1.0 / np.sqrt(d)
     s_task = np.empty((hq, n))
     for qh in range(hq):
-        a = attention(q[qh], k[qh // g], scale)       # [M, N]: A^(l, qh, c, m)
+        a = attention(q[qh], k[qh // g], scale, causal_tail)   # [M, N]: A^(l, qh, c, m)
         if v is not None:
             a = a * np.sqrt((v[qh // g] * v[qh // g]).sum(axis=1))[None, :]   # A^(w)
         s_task[qh] = _agg(a, agg_task, axis=0)        # eq. 14
@@ -214,7 +226,8 @@ def gather_heads(x: np.ndarray, idx: np.ndarray, n_keep, position_order: bool = 
 # --------------------------------------------------------------------------
 def compress(q_layers, k_layers, v_layers, budget: int, *, agg_task=AGG_MAX,
              agg_group=AGG_MEAN, agg_head=AGG_MEAN, add_head_mean=True, scale=None,
-             value_norm=False, position_order=False, min_per_layer=0, unstructured=False):
+             value_norm=False, position_order=False, min_per_layer=0, unstructured=False,
+             causal_tail=False):
     """Run the pass on one sequence.
 
     q_layers[l]: [Hq, M, d]; k_layers[l], v_layers[l]: [Hkv, N, d]; any of
@@ -229,7 +242,7 @@ def compress(q_layers, k_layers, v_layers, budget: int, *, agg_task=AGG_MAX,
     for l in range(lyr):
         s = score_layer(widen(q_layers[l]), widen(k_layers[l]), agg_task=agg_task,
                         agg_group=agg_group, add_head_mean=add_head_mean, scale=scale,
-                        v=widen(v_layers[l]) if value_norm else None)
+                        v=widen(v_layers[l]) if value_norm else None, causal_tail=causal_tail)
         idx, s_sorted = head_rank(s)
         s_all.append(s)
         idx_all.append(idx)

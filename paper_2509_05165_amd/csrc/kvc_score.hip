@@ -224,11 +224,50 @@ __global__ __launch_bounds__(256) void score_merge(SeqTable seq, int rows_per_se
 // weighted attention matrix of the value-norm appendix scales every entry of
 // column c of head h by the same non-negative number, which commutes with the
 // max / mean over task tokens and over the group, so it is applied here.
+//
+// chunks_per_head = 1: every row chunk holds whole query heads and its partial is
+// already a group partial.  chunks_per_head = J > 1 (window of J*256 task tokens):
+// row chunk g*J + j holds rows [256 j, 256 j + 256) of query head g and its
+// partial is the raw task aggregate of those rows (max of the log2-domain
+// logits, or sum of probabilities); the J pieces are joined, turned into the
+// task score (2^max, or sum / window) and only then aggregated over g.
 // ---------------------------------------------------------------------------
-__global__ void score_finish(const float* part, int row_chunks, int hkv, int total,
-                             float group_norm, int group_max, int add_head_mean, float* S,
-                             size_t layer_stride, const float* __restrict__ vnorm) {
+struct FinishArgs {
+  int row_chunks, hkv, total, group_max, add_head_mean, chunks_per_head, task_max;
+  float group_norm, inv_window;
+};
+
+__device__ __forceinline__ float finish_group_value(const float* part, const FinishArgs& a, int h,
+                                                    int c, const float* vnorm) {
+  float v;
+  if (a.chunks_per_head <= 1) {
+    v = part[((size_t)0 * a.hkv + h) * a.total + c];
+    for (int rc = 1; rc < a.row_chunks; ++rc) {
+      const float x = part[((size_t)rc * a.hkv + h) * a.total + c];
+      v = a.group_max ? fmaxf(v, x) : v + x;
+    }
+  } else {
+    const int heads = a.row_chunks / a.chunks_per_head;
+    v = 0.f;                                           // task scores are >= 0
+    for (int g = 0; g < heads; ++g) {
+      float tv = part[((size_t)(g * a.chunks_per_head) * a.hkv + h) * a.total + c];
+      for (int j = 1; j < a.chunks_per_head; ++j) {
+        const float x = part[((size_t)(g * a.chunks_per_head + j) * a.hkv + h) * a.total + c];
+        tv = a.task_max ? fmaxf(tv, x) : tv + x;
+      }
+      const float sv = a.task_max ? fast_exp2(tv) : tv * a.inv_window;
+      v = a.group_max ? fmaxf(v, sv) : v + sv;
+    }
+  }
+  v *= a.group_norm;
+  if (vnorm) v *= vnorm[(size_t)h * a.total + c];
+  return v;
+}
+
+__global__ void score_finish(const float* part, FinishArgs a, float* S, size_t layer_stride,
+                             const float* __restrict__ vnorm) {
   const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  const int hkv = a.hkv, total = a.total, add_head_mean = a.add_head_mean;
   if (c >= total) return;
   part += blockIdx.y * layer_stride;
   S += blockIdx.y * layer_stride;
@@ -237,13 +276,7 @@ __global__ void score_finish(const float* part, int row_chunks, int hkv, int tot
   for (int h0 = 0; h0 < hkv; h0 += 8) {
     // first sweep: values of up to 8 heads (kept so the in-place write is safe)
     for (int i = 0; i < 8 && h0 + i < hkv; ++i) {
-      float v = part[((size_t)0 * hkv + h0 + i) * total + c];
-      for (int rc = 1; rc < row_chunks; ++rc) {
-        const float x = part[((size_t)rc * hkv + h0 + i) * total + c];
-        v = group_max ? fmaxf(v, x) : v + x;
-      }
-      v *= group_norm;
-      if (vnorm) v *= vnorm[(size_t)(h0 + i) * total + c];
+      const float v = finish_group_value(part, a, h0 + i, c, vnorm);
       vals[i] = v;
       sum += v;
     }
@@ -256,16 +289,8 @@ __global__ void score_finish(const float* part, int row_chunks, int hkv, int tot
   // more than 8 KV heads: recompute values in a second sweep (part != S is
   // guaranteed by the launcher in that case)
   const float mean = add_head_mean ? sum / float(hkv) : 0.f;
-  for (int h = 0; h < hkv; ++h) {
-    float v = part[((size_t)0 * hkv + h) * total + c];
-    for (int rc = 1; rc < row_chunks; ++rc) {
-      const float x = part[((size_t)rc * hkv + h) * total + c];
-      v = group_max ? fmaxf(v, x) : v + x;
-    }
-    v *= group_norm;
-    if (vnorm) v *= vnorm[(size_t)h * total + c];
-    S[(size_t)h * total + c] = v + mean;
-  }
+  for (int h = 0; h < hkv; ++h)
+    S[(size_t)h * total + c] = finish_group_value(part, a, h, c, vnorm) + mean;
 }
 
 // ---------------------------------------------------------------------------
@@ -350,10 +375,17 @@ kvc_status launch_score(const Problem& pb, const void* const* q, const void* con
   const bool separate = L.row_chunks > 1 || pb.hkv > 8;
   float* vnorm = v ? reinterpret_cast<float*>(w + L.off_vnorm) : nullptr;
   const bool per_layer_finish = separate || vnorm != nullptr;
+  FinishArgs fa{};
+  fa.row_chunks = L.row_chunks; fa.hkv = pb.hkv; fa.total = int(pb.total);
+  fa.group_max = pb.agg_group == KVC_AGG_MAX; fa.add_head_mean = pb.add_head_mean;
+  fa.task_max = pb.agg_task == KVC_AGG_MAX;
+  // a window above 256 task tokens spreads every query head over window/256 row chunks
+  fa.chunks_per_head = (mfma_supported(pb) && pb.window > MF_RCHUNK) ? pb.window / MF_RCHUNK : 1;
+  fa.group_norm = fa.group_max ? 1.f : 1.f / float(pb.group);
+  fa.inv_window = 1.f / float(pb.window);
   const float c2 = pb.scale * LOG2E;
   const int total = int(pb.total);
   const int task_max = pb.agg_task == KVC_AGG_MAX, group_max = pb.agg_group == KVC_AGG_MAX;
-  const float group_norm = group_max ? 1.f : 1.f / float(pb.group);
   const bool mfma = mfma_supported(pb);
   const int chunk = mfma ? MF_CHUNK : GEN_CHUNK;
   const int chunks = int((pb.max_seqlen + chunk - 1) / chunk);
@@ -430,12 +462,12 @@ kvc_status launch_score(const Problem& pb, const void* const* q, const void* con
     }
     if (per_layer_finish)
       KVC_LAUNCH("score_finish", stream, score_finish<<<(total + 255) / 256, 256, 0, stream>>>(
-          part, L.row_chunks, pb.hkv, total, group_norm, group_max, pb.add_head_mean, S_l, 0, vnorm));
+          part, fa, S_l, 0, vnorm));
   }
   // emitted in place: one launch finishes every layer
   if (!per_layer_finish && pb.layers > 0 && total > 0)
     KVC_LAUNCH("score_finish", stream, score_finish<<<dim3((total + 255) / 256, pb.layers), 256, 0, stream>>>(
-        S, 1, pb.hkv, total, group_norm, group_max, pb.add_head_mean, S, size_t(pb.hkv) * total, nullptr));
+        S, fa, S, size_t(pb.hkv) * total, nullptr));
   return KVC_OK;
 }
 

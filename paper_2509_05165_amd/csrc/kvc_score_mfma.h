@@ -342,7 +342,10 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
           t0 = TASK_MAX ? fmaxf(t0, x[i]) : t0 + x[i];
           t1 = TASK_MAX ? fmaxf(t1, x[4 + i]) : t1 + x[4 + i];
         }
-        if (bpg == 8) {
+        if (bpg > 8) {
+          // the query head continues in other row chunks: hand on the raw task partial
+          gacc = TASK_MAX ? fmaxf(t0, t1) : t0 + t1;
+        } else if (bpg == 8) {
           const float tv = TASK_MAX ? fmaxf(t0, t1) : t0 + t1;
           gacc = TASK_MAX ? fast_exp2(tv) : tv * inv_window;
         } else {
@@ -527,9 +530,12 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
   }
 }
 
+// Windows up to 256 task tokens must divide 256 (a row chunk then holds whole
+// query heads); larger windows must be multiples of 256 (a query head then
+// spans window/256 whole row chunks).
 inline bool mfma_supported(const Problem& pb) {
-  return pb.dtype == KVC_BF16 && pb.d == MF_D && pb.window % 32 == 0 && pb.window <= MF_RCHUNK &&
-         MF_RCHUNK % pb.window == 0;
+  if (pb.dtype != KVC_BF16 || pb.d != MF_D || pb.window % 32 != 0) return false;
+  return pb.window <= MF_RCHUNK ? MF_RCHUNK % pb.window == 0 : pb.window % MF_RCHUNK == 0;
 }
 
 }  // namespace

@@ -34,6 +34,11 @@ SCORE_CASES = {
     "bf16-generic-m48": (1, dict(layers=1, window=48, hq=8, hkv=4, n=400), None),
     "bf16-varlen-batch": (3, dict(layers=1, batch=3, n_range=(200, 1400)), None),
     "bf16-12-kv-heads": (1, dict(layers=1, hq=24, hkv=12, n=300), None),
+    # task-aware shape: windows of several hundred task tokens, a query head spans row chunks
+    "bf16-mfma-m512-noGQA": (1, dict(layers=1, hq=2, hkv=2, window=512, n=600), None),
+    "bf16-mfma-m512-g2": (1, dict(layers=2, hq=4, hkv=2, window=512, n=2300), None),
+    "bf16-mfma-m1024-g4": (1, dict(layers=1, hq=8, hkv=2, window=1024, n=450), None),
+    "bf16-generic-m320": (1, dict(layers=1, hq=4, hkv=2, window=320, n=300), None),
 }
 
 
@@ -65,7 +70,8 @@ def test_score_matches_oracle(name):
     (kv.KVC_AGG_MEAN, kv.KVC_AGG_MEAN, 1), (kv.KVC_AGG_MAX, kv.KVC_AGG_MAX, 1),
     (kv.KVC_AGG_MEAN, kv.KVC_AGG_MAX, 0), (kv.KVC_AGG_MAX, kv.KVC_AGG_MEAN, 0)])
 @pytest.mark.parametrize("cid,over", [(0, dict(layers=1, hq=8, hkv=4)),
-                                      (1, dict(layers=1, n=900))])
+                                      (1, dict(layers=1, n=900)),
+                                      (1, dict(layers=1, hq=4, hkv=2, window=512, n=700))])
 def test_score_aggregator_variants(agg_task, agg_group, head_mean, cid, over):
     _say(f"score variants task={agg_task} group={agg_group} mean={head_mean} cfg={cid}")
     w = Workload(wl.get_config(cid, **over), seed=1)

@@ -199,3 +199,33 @@ def test_position_order_full_budget_is_the_identity_and_sets_agree():
             rows = a["idx"][l, h, :nl]
             np.testing.assert_array_equal(b["K_out"][l][h], k[l][h, np.sort(rows)])
             assert sorted(map(bytes, a["K_out"][l][h])) == sorted(map(bytes, b["K_out"][l][h]))
+
+
+# ---------------------------------------------------------------- causal tail
+def test_causal_tail_handworked():
+    g = GOLD["causal_tail"]
+    q, k = np.array(g["q"]), np.array(g["k"])
+    a = orc.attention(q[0], k[0], g["scale"], causal_tail=True)
+    np.testing.assert_allclose(a, np.array(g["attention"]), rtol=0, atol=1e-15)
+    np.testing.assert_allclose(orc.score_layer(q, k, scale=g["scale"], causal_tail=True), np.array(g["S"]), rtol=1e-14)
+    np.testing.assert_allclose(orc.score_layer(q, k, scale=g["scale"]), np.array(g["S_unmasked"]), rtol=1e-14)
+
+
+def test_causal_tail_rows_are_softmaxes_over_their_visible_prefix():
+    rng = np.random.default_rng(8)
+    m, n, d = 5, 11, 6
+    q, k = rng.standard_normal((m, d)), rng.standard_normal((n, d))
+    a = orc.attention(q, k, 0.3, causal_tail=True)
+    for mm in range(m):
+        vis = n - m + mm + 1                                   # keys 0 .. N-M+m
+        assert np.all(a[mm, vis:] == 0.0)
+        # brute force over the visible keys only
+        logits = [0.3 * sum(q[mm, j] * k[c, j] for j in range(d)) for c in range(vis)]
+        z = sum(math.exp(x) for x in logits)
+        np.testing.assert_allclose(a[mm, :vis], [math.exp(x) / z for x in logits], rtol=1e-13)
+    np.testing.assert_allclose(a.sum(axis=1), 1.0, rtol=1e-14)
+    # the last task token sees everything: its row equals the unmasked one; one task token = no mask
+    np.testing.assert_allclose(a[-1], orc.attention(q, k, 0.3)[-1], rtol=1e-14)
+    np.testing.assert_allclose(orc.attention(q[:1], k, 0.3, causal_tail=True), orc.attention(q[:1], k, 0.3), rtol=1e-14)
+    with pytest.raises(ValueError):
+        orc.attention(q, k[:4], 0.3, causal_tail=True)
