@@ -130,6 +130,12 @@ typedef struct kvc_params {
   int32_t unstructured;  /* 1: no head aggregation; the pool holds all Lyr*Hkv*N_b
                             rank-aligned scores and every head keeps its own prefix
                             (appendix on unstructured eviction) */
+  int32_t causal_tail;   /* 1: the M task tokens are the last M tokens of the context
+                            (task-agnostic setting, Section 3.2.1): task token m sits at
+                            position N_b-M+m and attends to cached keys at positions
+                            <= N_b-M+m only (softmax over those; the rest of its row of
+                            A is 0).  Needs N_b >= M.  0: no mask, the library's default
+                            reading. */
 } kvc_params;
 
 typedef struct kvc_inputs {

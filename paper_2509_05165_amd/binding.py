@@ -37,16 +37,16 @@ class KvcParams(C.Structure):
         ("agg_task", C.c_int32), ("agg_group", C.c_int32), ("agg_head", C.c_int32),
         ("add_head_mean", C.c_int32), ("softmax_scale", C.c_float),
         ("value_norm", C.c_int32), ("order", C.c_int32), ("min_per_layer", C.c_int32),
-        ("unstructured", C.c_int32),
+        ("unstructured", C.c_int32), ("causal_tail", C.c_int32),
     ]
 
     def __init__(self, batch, layers, hq, hkv, head_dim, window, dtype, agg_task=KVC_AGG_MAX,
                  agg_group=KVC_AGG_MEAN, agg_head=KVC_AGG_MEAN, add_head_mean=1,
                  softmax_scale=0.0, value_norm=0, order=KVC_ORDER_RANK, min_per_layer=0,
-                 unstructured=0):
+                 unstructured=0, causal_tail=0):
         super().__init__(batch, layers, hq, hkv, head_dim, window, dtype, agg_task, agg_group,
                          agg_head, add_head_mean, softmax_scale, value_norm, order,
-                         min_per_layer, unstructured)
+                         min_per_layer, unstructured, causal_tail)
 
 
 class _Inputs(C.Structure):

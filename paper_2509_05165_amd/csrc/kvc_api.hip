@@ -66,8 +66,8 @@ static kvc_status check_params(const kvc_params* p) {
   if (!(p->softmax_scale >= 0.0f) || !std::isfinite(p->softmax_scale)) {
     set_error("softmax_scale must be finite and >= 0"); return KVC_ERR_INVALID_ARG;
   }
-  if ((p->value_norm | p->unstructured) & ~1) {
-    set_error("value_norm and unstructured must be 0 or 1"); return KVC_ERR_INVALID_ARG;
+  if ((p->value_norm | p->unstructured | p->causal_tail) & ~1) {
+    set_error("value_norm, unstructured and causal_tail must be 0 or 1"); return KVC_ERR_INVALID_ARG;
   }
   if (p->order != KVC_ORDER_RANK && p->order != KVC_ORDER_POSITION) {
     set_error("unknown output order %d", p->order); return KVC_ERR_INVALID_ARG;
@@ -102,6 +102,10 @@ static kvc_status make_problem(const kvc_params* p, const int64_t* cu, Problem* 
   for (int b = 0; b < p->batch; ++b) {
     int64_t n = cu[b + 1] - cu[b];
     if (n < 0) { set_error("cu_seqlens must be non-decreasing"); return KVC_ERR_INVALID_ARG; }
+    if (p->causal_tail && n > 0 && n < p->window) {
+      set_error("causal_tail needs N_b >= window (sequence %d has %lld tokens)", b, (long long)n);
+      return KVC_ERR_INVALID_ARG;
+    }
     if (n > mx) mx = n;
   }
   if (cu[p->batch] >= (int64_t(1) << 31)) {
@@ -112,7 +116,7 @@ static kvc_status make_problem(const kvc_params* p, const int64_t* cu, Problem* 
   pb->dtype = p->dtype; pb->agg_task = p->agg_task; pb->agg_group = p->agg_group;
   pb->agg_head = p->agg_head; pb->add_head_mean = p->add_head_mean;
   pb->value_norm = p->value_norm; pb->order = p->order; pb->min_per_layer = p->min_per_layer;
-  pb->unstructured = p->unstructured;
+  pb->unstructured = p->unstructured; pb->causal_tail = p->causal_tail;
   pb->sel_rows = p->unstructured ? p->layers * p->hkv : p->layers;
   pb->scale = p->softmax_scale > 0.0f ? p->softmax_scale
                                       : 1.0f / std::sqrt(float(p->head_dim));

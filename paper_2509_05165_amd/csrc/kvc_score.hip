@@ -57,8 +57,8 @@ __device__ __forceinline__ void gen_load_ktile(float* lds, const T* k_head, int 
 template <typename T>
 __global__ __launch_bounds__(256) void score_stats_generic(
     const T* __restrict__ q_layer, const T* __restrict__ k_layer, SeqTable seq, int hq, int group,
-    int window, int d, int total, float c2, int chunk_keys, int max_chunks, float* part_m,
-    float* part_s) {
+    int window, int d, int total, float c2, int chunk_keys, int max_chunks, int causal,
+    float* part_m, float* part_s) {
   extern __shared__ float lds[];
   const int b = blockIdx.z;
   const int tok0 = seq.cu[b], n = seq.cu[b + 1] - tok0;
@@ -90,9 +90,11 @@ __global__ __launch_bounds__(256) void score_stats_generic(
       const T* qrow = q_head + (size_t)m * d;
       float acc = 0.f;
       for (int j = 0; j < d; ++j) acc = fmaf(load_as_float(qrow + j), krow[j], acc);
-      const float t = valid ? acc * c2 : NEG_BIG;
+      // causal tail: task token m sees keys at positions <= n - window + m
+      const bool seen = valid && (!causal || key0 + kc <= n - window + m);
+      const float t = seen ? acc * c2 : NEG_BIG;
       const float mn = fmaxf(mrun[i], t);
-      srun[i] = srun[i] * fast_exp2(mrun[i] - mn) + (valid ? fast_exp2(t - mn) : 0.f);
+      srun[i] = srun[i] * fast_exp2(mrun[i] - mn) + (seen ? fast_exp2(t - mn) : 0.f);
       mrun[i] = mn;
     }
   }
@@ -121,7 +123,7 @@ template <typename T>
 __global__ __launch_bounds__(256) void score_emit_generic(
     const T* __restrict__ q_layer, const T* __restrict__ k_layer, SeqTable seq, int hq, int group,
     int window, int d, int total, float c2, int chunk_keys, const float* __restrict__ lse2,
-    int task_max, int group_max, float* __restrict__ out /* [Hkv][T] un-normalised */) {
+    int task_max, int group_max, int causal, float* __restrict__ out /* [Hkv][T] un-normalised */) {
   extern __shared__ float lds[];
   float* red = lds + GEN_TILE * (d + 1);  // [GEN_MGROUPS][GEN_TILE]
   const int b = blockIdx.z, h = blockIdx.y;
@@ -154,6 +156,7 @@ __global__ __launch_bounds__(256) void score_emit_generic(
           float acc = 0.f;
           for (int j = 0; j < d; ++j) acc = fmaf(load_as_float(qrow + j), krow[j], acc);
           const float t = acc * c2 - lse_head[m];
+          if (causal && key0 + kc > n - window + m) continue;      // hidden from task token m
           v = task_max ? fmaxf(v, t) : v + fast_exp2(t);
         }
         red[mg * GEN_TILE + kc] = v;
@@ -402,7 +405,7 @@ kvc_status launch_score(const Problem& pb, const void* const* q, const void* con
 #define KVC_SCORE_MFMA(NAME, EMIT, TMAX, WQ, PM, PS, LSE, OUT)                                   \
   KVC_LAUNCH(NAME, stream, score_mfma<EMIT, TMAX, WQ><<<grid, MF_THREADS, 0, stream>>>(           \
       ql, kl, pb.seq, pb.hq, pb.group, pb.window, total, c2, chunk, L.row_chunks,                \
-      PM, PS, LSE, group_max, OUT))
+      PM, PS, LSE, group_max, pb.causal_tail, OUT))
 #define KVC_SCORE_MFMA_WQ(NAME, EMIT, TMAX, PM, PS, LSE, OUT)                     \
   do {                                                                            \
     if (nqb0 <= 2) { KVC_SCORE_MFMA(NAME, EMIT, TMAX, 1, PM, PS, LSE, OUT); }       \
@@ -429,23 +432,23 @@ kvc_status launch_score(const Problem& pb, const void* const* q, const void* con
         const uint16_t* kl = static_cast<const uint16_t*>(k[l]);
         KVC_LAUNCH("score_stats_generic", stream, score_stats_generic<uint16_t><<<gs, 256, lds_s, stream>>>(
             ql, kl, pb.seq, pb.hq, pb.group, pb.window, pb.d, total, c2, chunk, L.max_chunks,
-            part_m, part_s));
+            pb.causal_tail, part_m, part_s));
         KVC_LAUNCH("score_merge", stream, score_merge<<<(L.rows_layer + MERGE_ROWS - 1) / MERGE_ROWS, 256, 0, stream>>>(
             pb.seq, rows_per_seq, chunk, part_m, part_s, lse2));
         KVC_LAUNCH("score_emit_generic", stream, score_emit_generic<uint16_t><<<ge, 256, lds_e, stream>>>(
             ql, kl, pb.seq, pb.hq, pb.group, pb.window, pb.d, total, c2, chunk, lse2, task_max,
-            group_max, part));
+            group_max, pb.causal_tail, part));
       } else {
         const float* ql = static_cast<const float*>(q[l]);
         const float* kl = static_cast<const float*>(k[l]);
         KVC_LAUNCH("score_stats_generic", stream, score_stats_generic<float><<<gs, 256, lds_s, stream>>>(
             ql, kl, pb.seq, pb.hq, pb.group, pb.window, pb.d, total, c2, chunk, L.max_chunks,
-            part_m, part_s));
+            pb.causal_tail, part_m, part_s));
         KVC_LAUNCH("score_merge", stream, score_merge<<<(L.rows_layer + MERGE_ROWS - 1) / MERGE_ROWS, 256, 0, stream>>>(
             pb.seq, rows_per_seq, chunk, part_m, part_s, lse2));
         KVC_LAUNCH("score_emit_generic", stream, score_emit_generic<float><<<ge, 256, lds_e, stream>>>(
             ql, kl, pb.seq, pb.hq, pb.group, pb.window, pb.d, total, c2, chunk, lse2, task_max,
-            group_max, part));
+            group_max, pb.causal_tail, part));
       }
     }
     // with separate partials (or one buffer of value norms) each layer is finished

@@ -162,12 +162,17 @@ __device__ __forceinline__ void lds_dma16_s(const void* sbase, uint32_t voff, ui
 //   the workgroup waits for tile t+1, meets at a barrier, starts the load of
 //   tile t+2 into the buffer of tile t and (EMIT) writes out tile t-1; the last
 //   phase already prefetches the first fragments of tile t+1.
+//
+// causal != 0: task token m sits at position n - window + m of its sequence and
+// sees keys at positions <= that only.  Tiles that lie wholly below position
+// n - window + 1 are visible to every row and go through the pipeline; the few
+// tiles above it are processed one key tile at a time with the mask applied.
 template <bool EMIT, bool TASK_MAX, int WQ>
 __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
     const uint16_t* __restrict__ q_layer, const uint16_t* __restrict__ k_layer, SeqTable seq,
     int hq, int group, int window, int total, float c2, int chunk_keys, int row_chunks,
     float* __restrict__ part_m, float* __restrict__ part_s, const float* __restrict__ lse2,
-    int group_max, float* __restrict__ out) {
+    int group_max, int causal, float* __restrict__ out) {
   constexpr int WK = 4 / WQ;        // waves along the keys
   constexpr int NT = 4 / WK;        // 32-key tiles per wave per macro tile
   constexpr bool PIPE = NT % 2 == 0;
@@ -361,6 +366,11 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
   };
   // One key tile at a time with masking of keys past `keys_here` (ragged tile, or
   // every tile when the wave has an odd number of key tiles).
+  // causal tail: task-token index of the first row of each of the wave's q blocks
+  // (blocks are 32-aligned and window % 32 == 0, so a block never wraps) and the
+  // last key position every row sees
+  const int mbase[2] = {(row0 + (wq * 2) * 32) % window, (row0 + (wq * 2 + 1) * 32) % window};
+  const int all_see = n - window;
   auto serial_tile = [&](int t, int keys_here) {
     const unsigned char* kb = kbuf[t & 1];
     for (int j = 0; j < NT; ++j) {
@@ -369,15 +379,31 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
       uint4 kf[8];
       load_frags(kf, kb + kt * 8192);
       mfma_tile(acc[0], kf);
+      const int kpos0 = key_begin + t * MF_TILE + kt * 32;       // position of the tile's first key
+      const bool masked = causal && kpos0 + 31 > all_see;        // wave-uniform
       if (!EMIT) {
         if (kt * 32 + 32 > keys_here) {      // keys past the sequence drop out
 #pragma unroll
           for (int r = 0; r < 16; ++r)
             if (kt * 32 + acc_row(r, half) >= keys_here) { acc[0][0][r] = NEG_BIG; acc[0][1][r] = NEG_BIG; }
         }
+        if (masked) {                         // rows = keys, my column = one task token
+#pragma unroll
+          for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+              if (kpos0 + acc_row(r, half) > all_see + mbase[qb] + col) acc[0][qb][r] = NEG_BIG;
+        }
         stats_fold(acc[0][0], c2, mrun[0], srun[0]);
         stats_fold(acc[0][1], c2, mrun[1], srun[1]);
       } else {
+        if (masked) {                         // rows = task tokens, my column = one key
+#pragma unroll
+          for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+              if (kpos0 + col > all_see + mbase[qb] + acc_row(r, half)) acc[0][qb][r] = NEG_BIG;
+        }
         emit_store(acc[0], t % 3, kt);
       }
     }
@@ -389,6 +415,7 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
   wait_vmcnt<0>();
   if (EMIT) lse_s[threadIdx.x] = my_nl;
   if (ntiles > 1) issue_tile(1);
+  int issued = ntiles > 1 ? 1 : 0;            // highest tile requested so far
   __syncthreads();
 
   // EMIT: minus lse2 of the 16 accumulator rows of each q block held by this lane
@@ -407,13 +434,16 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
     }
   }
 
+  // tiles [0, npipe) run through the software pipeline
+  int npipe = PIPE ? nfull : 0;
+  if (causal) npipe = max(0, min(npipe, (all_see + 1 - key_begin) / MF_TILE));
   if (PIPE) {
     uint4 kf[8];
     load_frags(kf, kbuf[0] + wk * 8192);
     // Two workgroups share a CU and the hardware favours the older one; alternating
     // the wave priority per tile keeps them advancing at the same pace.
     const int prio_phase = (blockIdx.y * 2 >= gridDim.y) ? 1 : 0;
-    for (int it = 0; it < nfull; ++it) {
+    for (int it = 0; it < npipe; ++it) {
       if ((it + prio_phase) & 1) __builtin_amdgcn_s_setprio(1);
       else __builtin_amdgcn_s_setprio(0);
       const unsigned char* kb = kbuf[it & 1];
@@ -429,9 +459,9 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
           if (it + 1 < ntiles) wait_vmcnt<0>();
           __syncthreads();
           if (EMIT && it > 0) epilogue(it - 1, MF_TILE);
-          if (it + 2 < ntiles) issue_tile(it + 2);
-          // next full tile's first fragments (or a harmless re-read of this tile's)
-          nkb = (it + 1 < nfull ? kbuf[(it + 1) & 1] : kb) + wk * 8192;
+          if (it + 2 < ntiles) { issue_tile(it + 2); issued = it + 2; }
+          // next pipelined tile's first fragments (or a harmless re-read of this tile's)
+          nkb = (it + 1 < npipe ? kbuf[(it + 1) & 1] : kb) + wk * 8192;
         }
         StatsCarry carry;
         float ev[2];
@@ -469,33 +499,26 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
       }
     }
     __builtin_amdgcn_s_setprio(0);
-    // the last key tile of the last full macro tile is still pending
+    // the last key tile of the last pipelined macro tile is still pending
     if (!EMIT) {
       stats_fold(acc[1][0], c2, mrun[0], srun[0]);
       stats_fold(acc[1][1], c2, mrun[1], srun[1]);
-    } else if (nfull > 0) {
-      emit_store(acc[1], (nfull - 1) % 3, wk + (NT - 1) * WK);
-    }
-    if (tail > 0) {
-      wait_vmcnt<0>();
-      __syncthreads();
-      if (EMIT && nfull > 0) epilogue(nfull - 1, MF_TILE);
-      serial_tile(nfull, tail);
-      __syncthreads();
-      if (EMIT) epilogue(nfull, tail);
-    } else {
-      __syncthreads();
-      if (EMIT && nfull > 0) epilogue(nfull - 1, MF_TILE);
-    }
-  } else {
-    for (int it = 0; it < ntiles; ++it) {
-      serial_tile(it, it < nfull ? MF_TILE : tail);
-      wait_vmcnt<0>();
-      __syncthreads();
-      if (it + 2 < ntiles) issue_tile(it + 2);
-      if (EMIT) epilogue(it, it < nfull ? MF_TILE : tail);
+    } else if (npipe > 0) {
+      emit_store(acc[1], (npipe - 1) % 3, wk + (NT - 1) * WK);
     }
   }
+  // The other tiles one key tile at a time: the ragged last tile, tiles under the
+  // causal mask, every tile when the wave has an odd number of key tiles.  Tile t
+  // is in buffer t&1; tile t+1 is requested once every wave is done with tile t-1.
+  for (int t = npipe; t < ntiles; ++t) {
+    wait_vmcnt<0>();
+    __syncthreads();
+    if (EMIT && t > 0) epilogue(t - 1, MF_TILE);
+    if (issued < t + 1 && t + 1 < ntiles) { issue_tile(t + 1); issued = t + 1; }
+    serial_tile(t, t < nfull ? MF_TILE : tail);
+  }
+  __syncthreads();
+  if (EMIT && ntiles > 0) epilogue(ntiles - 1, tail > 0 ? tail : MF_TILE);
 
   if (!EMIT) {
     // lanes l and l+32 hold the same query over different keys

@@ -136,6 +136,7 @@ def test_variant_parameter_checks():
     expect(1, kv.kvc_workspace_size, P(order=2), 100, 100)
     expect(1, kv.kvc_workspace_size, P(min_per_layer=-1), 100, 100)
     expect(1, kv.kvc_workspace_size, P(unstructured=3), 100, 100)
+    expect(1, kv.kvc_workspace_size, P(causal_tail=2), 100, 100)
     # the variants never need less workspace than the plain pass
     base = kv.kvc_workspace_size(P(), 50000, 50000)
     assert kv.kvc_workspace_size(P(value_norm=1), 50000, 50000) >= base
@@ -150,6 +151,8 @@ def test_variant_argument_checks_run_before_any_gpu_call():
     expect(1, kv.kvc_global_select, P(min_per_layer=10), FAKE, cu, [19], 0, FAKE, FAKE, FAKE, 1 << 30)
     # unstructured: the budget counts (head, token) entries, up to layers*hkv*N
     expect(1, kv.kvc_global_select, P(unstructured=1), FAKE, cu, [2 * 4 * 100 + 1], 0, FAKE, FAKE, FAKE, 1 << 30)
+    # the causal tail needs at least as many cached tokens as task tokens
+    expect(1, kv.kvc_score, P(causal_tail=1), [FAKE] * 2, [FAKE] * 2, [0, 63], FAKE, FAKE, 1 << 30)
     # position order needs workspace in the gather stage
     expect(3, kv.kvc_gather, P(order=kv.KVC_ORDER_POSITION), [FAKE] * 2, [FAKE] * 2, FAKE, FAKE, FAKE,
            cu, 5, FAKE, FAKE, 0)

@@ -329,3 +329,66 @@ def test_compress_unstructured_end_to_end():
             chosen[sel] = True
             s_o = ref["S"][l, h]
             assert chosen[s_o > tau * (1 + EPS)].all() and not chosen[s_o < tau * (1 - EPS)].any()
+
+
+# ---------------------------------------------------------------- causal tail
+CAUSAL_CASES = {
+    "tiny-f32": (0, dict(layers=2), {}),
+    "f32-ragged-m20": (0, dict(layers=1, hq=6, hkv=2, n=777, window=20, head_dim=32), {}),
+    "bf16-mfma-one-tile": (1, dict(layers=1, n=100), {}),
+    "bf16-mfma-n-equals-m": (1, dict(layers=1, n=64), {}),
+    "bf16-mfma-ragged": (1, dict(layers=2, n=1500), {}),
+    "bf16-mfma-mask-crosses-chunk": (1, dict(layers=1, n=2048 + 30), {}),
+    "bf16-mfma-mask-ends-on-tile": (1, dict(layers=1, n=2048 + 128), {}),
+    "bf16-mfma-mean-task": (1, dict(layers=1, n=900), dict(agg_task=kv.KVC_AGG_MEAN)),
+    "bf16-mfma-m128-gqa8": (4, dict(layers=1, n=700), {}),
+    "bf16-mfma-m32-g2": (1, dict(layers=1, hq=8, hkv=4, window=32, n=500), {}),
+    "bf16-mfma-noGQA": (1, dict(layers=1, hq=4, hkv=4, n=700), {}),
+    "bf16-mfma-m512": (1, dict(layers=1, hq=4, hkv=2, window=512, n=600), {}),
+    "bf16-mfma-m512-two-chunks": (1, dict(layers=1, hq=2, hkv=2, window=512, n=2300), {}),
+    "bf16-generic-m48": (1, dict(layers=1, window=48, hq=8, hkv=4, n=400), {}),
+    "bf16-varlen-batch": (3, dict(layers=1, batch=3, n_range=(200, 1400)), {}),
+}
+
+
+@pytest.mark.parametrize("name", list(CAUSAL_CASES))
+def test_causal_tail_scores_match_oracle(name):
+    cid, over, pkw = CAUSAL_CASES[name]
+    _say(f"causal {name}")
+    cfg = wl.get_config(cid, **over)
+    w = Workload(cfg)
+    dw = DeviceWorkload(w)
+    p = w.params(causal_tail=1, **pkw)
+    S = torch.zeros((cfg.layers, cfg.hkv, w.total), dtype=torch.float32, device="cuda")
+    kv.kvc_score(p, dw.ptrs(dw.q), dw.ptrs(dw.k), w.cu, S.data_ptr(), dw.ws.data_ptr(),
+                 dw.ws_bytes, stream())
+    torch.cuda.synchronize()
+    got = S.cpu().numpy()
+    worst = 0.0
+    for b in range(cfg.batch):
+        lo, hi = int(w.cu[b]), int(w.cu[b + 1])
+        for l in range(cfg.layers):
+            ref = orc.score_layer(orc.widen(w.seq[b][l][0]), orc.widen(w.seq[b][l][1]), causal_tail=True,
+                                  agg_task=pkw.get("agg_task", orc.AGG_MAX))
+            np.testing.assert_allclose(got[l][:, lo:hi], ref, rtol=EPS, atol=0)
+            worst = max(worst, float(np.max(np.abs(got[l][:, lo:hi] - ref) / ref)))
+            # the mask matters: the last key is seen by one task token only
+            plain = orc.score_layer(orc.widen(w.seq[b][l][0]), orc.widen(w.seq[b][l][1]),
+                                    agg_task=pkw.get("agg_task", orc.AGG_MAX))
+            if cfg.window > 1:
+                assert not np.allclose(plain, ref, rtol=1e-3)
+    assert worst < 1e-4, worst
+
+
+def test_compress_causal_tail_end_to_end():
+    cfg = wl.get_config(1, layers=3, n=2200)
+    w = Workload(cfg)
+    dw = DeviceWorkload(w)
+    got = _run_variant(w, dw, causal_tail=1)
+    ref = w.oracle(causal_tail=True)[0]
+    np.testing.assert_allclose(got["S"], ref["S"], rtol=EPS)
+    lens = got["lengths"][0]
+    assert int(lens.sum()) == w.budgets[0]
+    tau = ref["tau"]
+    for l in range(cfg.layers):
+        assert int((ref["I"][l] > tau * (1 + EPS)).sum()) <= int(lens[l]) <= int((ref["I"][l] >= tau * (1 - EPS)).sum())
