@@ -7,6 +7,10 @@
 // stable, which yields the ascending-index order of equal scores for free.
 // Within a tile every wave ranks its items with ballot-based digit matching
 // and lane prefix counts; per-wave digit counters live in LDS.
+//
+// A segment that fits one tile (n <= 8192) never leaves the chip between the
+// passes: the digit-ordered staging area of one pass is the input of the next,
+// global memory sees one read of the scores and one write of the result.
 #include "kvc_internal.h"
 
 namespace kvc {
@@ -63,7 +67,9 @@ struct RankShared {
 // last pass writes scores and positions; the others move (key, value) pairs.
 // Tiles are processed in order; item (wave w, slot e, lane l) of a tile is
 // element base + w*64*ITEMS + e*64 + l, which is also its order inside the tile.
-template <int PASS>
+// LIN / LOUT (single-tile segments only): the pass reads its (key, value) pairs
+// from / leaves them in the LDS staging area, in slot order.
+template <int PASS, bool LIN, bool LOUT>
 __device__ __forceinline__ void radix_pass(RankShared& sh, int n, const float* __restrict__ src_f,
                                            const uint32_t* __restrict__ src_k,
                                            const int32_t* __restrict__ src_i,
@@ -101,14 +107,18 @@ __device__ __forceinline__ void radix_pass(RankShared& sh, int n, const float* _
     const int pos = (BASE) + woff + e * 64;                    \
     const int cpos = pos < n ? pos : n - 1;                    \
     if (PASS == 0) { K[e] = __float_as_uint(src_f[cpos]); V[e] = cpos; } \
+    else if (LIN) { K[e] = sh.stage_k[cpos]; V[e] = sh.stage_v[cpos]; }  \
     else { K[e] = src_k[cpos]; V[e] = src_i[cpos]; }           \
   }
   KVC_RANK_LOAD_TILE(0, key, val)
+  // (explicit, so that the loop body starts with no load the compiler still has to
+  // wait for: see the wait before the scatter)
+  if (!LIN) __builtin_amdgcn_s_waitcnt(0x0F70);
 
   for (int base = 0; base < n; base += RK_TILE) {
     // next tile's loads fly while this one is ranked and scattered
     const int nbase = base + RK_TILE < n ? base + RK_TILE : base;
-    KVC_RANK_LOAD_TILE(nbase, nkey, nval)
+    if (!LIN && !LOUT) { KVC_RANK_LOAD_TILE(nbase, nkey, nval) }   // a single tile has no next one
     if (PASS == 0) {
 #pragma unroll
       for (int e = 0; e < RK_ITEMS; ++e) key[e] = desc_key(__uint_as_float(key[e]));
@@ -178,8 +188,19 @@ __device__ __forceinline__ void radix_pass(RankShared& sh, int n, const float* _
       }
     }
     lds_barrier();
+    // The tile's items now live in the staging area, so the registers can take the
+    // next tile.  The wait is explicit and placed before the scatter: loads and
+    // stores share one in-order counter, and left to the compiler the wait for the
+    // prefetched loads lands in the next tile's ranking, behind this tile's stores.
+    if (!LIN && !LOUT) {
+      __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+#pragma unroll
+      for (int e = 0; e < RK_ITEMS; ++e) { key[e] = nkey[e]; val[e] = nval[e]; }
+    }
     // consecutive threads write consecutive global slots within a digit run
+    // (single tile with LOUT: slot order is the order of this pass; it stays in LDS)
     const int tile_n = min(RK_TILE, n - base);
+    if (!LOUT) {
 #pragma unroll
     for (int e = 0; e < RK_ITEMS; ++e) {
       const int slot = e * RK_THREADS + tid;
@@ -196,8 +217,7 @@ __device__ __forceinline__ void radix_pass(RankShared& sh, int n, const float* _
         }
       }
     }
-#pragma unroll
-    for (int e = 0; e < RK_ITEMS; ++e) { key[e] = nkey[e]; val[e] = nval[e]; }
+    }
   }
 #undef KVC_RANK_LOAD_TILE
   // the next pass reads what this one scattered: full fence + barrier
@@ -236,10 +256,17 @@ __global__ __launch_bounds__(RK_THREADS) void head_rank_kernel(
   }
   __syncthreads();
 
-  radix_pass<0>(sh, n, src_f, nullptr, nullptr, a_keys, a_idx, nullptr);
-  radix_pass<1>(sh, n, nullptr, a_keys, a_idx, b_keys, b_idx, nullptr);
-  radix_pass<2>(sh, n, nullptr, b_keys, b_idx, a_keys, a_idx, nullptr);
-  radix_pass<3>(sh, n, nullptr, a_keys, a_idx, nullptr, b_idx, sorted_out + seg);
+  if (n <= RK_TILE) {   // one tile: the passes hand the data on through LDS
+    radix_pass<0, false, true>(sh, n, src_f, nullptr, nullptr, nullptr, nullptr, nullptr);
+    radix_pass<1, true, true>(sh, n, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr);
+    radix_pass<2, true, true>(sh, n, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr);
+    radix_pass<3, true, false>(sh, n, nullptr, nullptr, nullptr, nullptr, b_idx, sorted_out + seg);
+    return;
+  }
+  radix_pass<0, false, false>(sh, n, src_f, nullptr, nullptr, a_keys, a_idx, nullptr);
+  radix_pass<1, false, false>(sh, n, nullptr, a_keys, a_idx, b_keys, b_idx, nullptr);
+  radix_pass<2, false, false>(sh, n, nullptr, b_keys, b_idx, a_keys, a_idx, nullptr);
+  radix_pass<3, false, false>(sh, n, nullptr, a_keys, a_idx, nullptr, b_idx, sorted_out + seg);
 }
 
 // grid: (token blocks, layers)

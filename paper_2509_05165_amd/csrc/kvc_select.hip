@@ -137,36 +137,41 @@ __global__ __launch_bounds__(SEL_THREADS) void select_count(
     atomicAdd(&counts[((size_t)b * layers + blockIdx.y) * 2 + threadIdx.x], sh[threadIdx.x]);
 }
 
-// one thread: lengths, offsets, tau
+// One thread per sequence.  The retained total of a sequence is its budget (known
+// on the host), so every thread derives its own first offset from the table.
 __global__ void select_finalize(SeqTable seq, int layers, int floor_rank, BudgetTable budget,
                                 const SelState* __restrict__ state,
                                 const uint32_t* __restrict__ counts, float* tau,
                                 int32_t* lengths, int64_t* offsets) {
-  if (blockIdx.x != 0 || threadIdx.x != 0) return;
-  int64_t off = 0;
-  for (int b = 0; b < seq.batch; ++b) {
-    const int64_t want = budget.b[b];
-    const int n_b = seq.cu[b + 1] - seq.cu[b];
-    const int64_t kept_first = floor_rank < n_b ? floor_rank : n_b;   // the floor entries
-    if (tau) tau[b] = want > 0 ? ordered_to_float(state[b].prefix) : __builtin_inff();
-    int64_t above = 0;
-    for (int l = 0; l < layers; ++l) above += counts[((size_t)b * layers + l) * 2];
-    int64_t ties_left = want - above;
-    for (int l = 0; l < layers; ++l) {
-      int64_t len = kept_first;
-      if (want > 0) {
-        const int64_t gt = counts[((size_t)b * layers + l) * 2];
-        const int64_t eq = counts[((size_t)b * layers + l) * 2 + 1];
-        const int64_t take = eq < ties_left ? eq : ties_left;
-        ties_left -= take;
-        len += gt + take;
-      }
-      lengths[b * layers + l] = (int32_t)len;
-      offsets[b * layers + l] = off;
-      off += len;
-    }
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= seq.batch) return;
+  int64_t off = 0;       // rows retained by the sequences before mine
+  for (int p = 0; p < b; ++p) {
+    const int n_p = seq.cu[p + 1] - seq.cu[p];
+    off += budget.b[p] + (int64_t)layers * (floor_rank < n_p ? floor_rank : n_p);
   }
-  offsets[seq.batch * layers] = off;
+  const int64_t want = budget.b[b];
+  const int n_b = seq.cu[b + 1] - seq.cu[b];
+  const int64_t kept_first = floor_rank < n_b ? floor_rank : n_b;   // the floor entries
+  if (tau) tau[b] = want > 0 ? ordered_to_float(state[b].prefix) : __builtin_inff();
+  int64_t above = 0;
+  if (want > 0)
+    for (int l = 0; l < layers; ++l) above += counts[((size_t)b * layers + l) * 2];
+  int64_t ties_left = want - above;
+  for (int l = 0; l < layers; ++l) {
+    int64_t len = kept_first;
+    if (want > 0) {
+      const int64_t gt = counts[((size_t)b * layers + l) * 2];
+      const int64_t eq = counts[((size_t)b * layers + l) * 2 + 1];
+      const int64_t take = eq < ties_left ? eq : ties_left;
+      ties_left -= take;
+      len += gt + take;
+    }
+    lengths[b * layers + l] = (int32_t)len;
+    offsets[b * layers + l] = off;
+    off += len;
+  }
+  if (b == seq.batch - 1) offsets[seq.batch * layers] = off;
 }
 
 struct SelectLayout { size_t off_hist, off_counts, off_state, total; int words; };

@@ -66,6 +66,9 @@ _CONFIGS = {
                       n_range=(4096, 32768), key_lognormal_sigma=0.5),
     4: WorkloadConfig(4, "deep-gqa8-64k", 1, 80, 64, 8, 128, 128, "bf16", 15, n=65536,
                       q_scale_ramp=(0.5, 2.0)),
+    # the regime of the paper's own evaluation (Section 4.1: 4096-token contexts,
+    # Section 4.2: an 8B model of 32 layers, 32/8 heads): many short sequences
+    5: WorkloadConfig(5, "llama3-8b-4k-b32", 32, 32, 32, 8, 128, 64, "bf16", 50, n=4096),
 }
 
 
