@@ -22,7 +22,7 @@ namespace kvc {
 namespace {
 
 constexpr int GA_THREADS = 256;
-constexpr int GA_BATCH = 4;   // row groups in flight per lane
+constexpr int GA_BATCH = 2;   // row groups in flight per lane (measured: 2 beats 1, 3, 4 and 8)
 
 // Each wave takes 64 consecutive rows of the output pool.  Lane i first resolves
 // pool row (group*64 + i): which (sequence, layer) block it lies in (binary
