@@ -136,6 +136,13 @@ typedef struct kvc_params {
                             <= N_b-M+m only (softmax over those; the rest of its row of
                             A is 0).  Needs N_b >= M.  0: no mask, the library's default
                             reading. */
+  int32_t keep_first;    /* forced retention (not part of the paper's method; the sink /
+                            recent-window conventions of its related work): the first
+                            keep_first and the last keep_last tokens of every sequence
+                            get S = +inf in every head of every layer, rank first
+                            (ascending position) and are retained whenever
+                            budget >= rows * (number of forced tokens) */
+  int32_t keep_last;     /* see keep_first */
 } kvc_params;
 
 typedef struct kvc_inputs {

@@ -46,6 +46,12 @@ Variants beyond the default pass (each off unless asked for):
   task token m sits at position N-M+m and attends to the cached keys at
   positions <= N-M+m only; its softmax runs over those keys and the other
   entries of its row of A are 0.  Needs N >= M.
+* forced retention (not in the paper's method; the attention-sink and
+  recent-window conventions its related-work section describes): the first
+  keep_first and the last keep_last tokens of the context get the score +inf in
+  every head of every layer, so they rank first (ascending position among
+  themselves) and are retained whenever the budget allows (B >= Lyr * number of
+  forced tokens).
 * unstructured selection (Appendix on unstructured eviction): the head
   aggregation is skipped, the pool holds all Lyr*Hkv*N rank-aligned scores,
   the budget counts (head, token) entries and every head keeps its own prefix
@@ -134,6 +140,19 @@ def score_layer(q, k, *, agg_task=AGG_MAX, agg_group=AGG_MEAN, add_head_mean=Tru
     if add_head_mean:
         return s_group + s_group.sum(axis=0, keepdims=True) / hkv  # augmentation
     return s_group
+
+
+def force_keep(s: np.ndarray, keep_first: int, keep_last: int) -> np.ndarray:
+    """Scores with the first keep_first and the last keep_last tokens set to +inf."""
+    n = s.shape[-1]
+    if keep_first < 0 or keep_last < 0:
+        raise ValueError("keep_first / keep_last must be >= 0")
+    if keep_first == 0 and keep_last == 0:
+        return s
+    s = s.copy()
+    s[..., :min(keep_first, n)] = np.inf
+    s[..., max(n - keep_last, 0):] = np.inf
+    return s
 
 
 # --------------------------------------------------------------------------
@@ -227,7 +246,7 @@ def gather_heads(x: np.ndarray, idx: np.ndarray, n_keep, position_order: bool = 
 def compress(q_layers, k_layers, v_layers, budget: int, *, agg_task=AGG_MAX,
              agg_group=AGG_MEAN, agg_head=AGG_MEAN, add_head_mean=True, scale=None,
              value_norm=False, position_order=False, min_per_layer=0, unstructured=False,
-             causal_tail=False):
+             causal_tail=False, keep_first=0, keep_last=0):
     """Run the pass on one sequence.
 
     q_layers[l]: [Hq, M, d]; k_layers[l], v_layers[l]: [Hkv, N, d]; any of
@@ -243,6 +262,7 @@ def compress(q_layers, k_layers, v_layers, budget: int, *, agg_task=AGG_MAX,
         s = score_layer(widen(q_layers[l]), widen(k_layers[l]), agg_task=agg_task,
                         agg_group=agg_group, add_head_mean=add_head_mean, scale=scale,
                         v=widen(v_layers[l]) if value_norm else None, causal_tail=causal_tail)
+        s = force_keep(s, keep_first, keep_last)
         idx, s_sorted = head_rank(s)
         s_all.append(s)
         idx_all.append(idx)

@@ -38,15 +38,16 @@ class KvcParams(C.Structure):
         ("add_head_mean", C.c_int32), ("softmax_scale", C.c_float),
         ("value_norm", C.c_int32), ("order", C.c_int32), ("min_per_layer", C.c_int32),
         ("unstructured", C.c_int32), ("causal_tail", C.c_int32),
+        ("keep_first", C.c_int32), ("keep_last", C.c_int32),
     ]
 
     def __init__(self, batch, layers, hq, hkv, head_dim, window, dtype, agg_task=KVC_AGG_MAX,
                  agg_group=KVC_AGG_MEAN, agg_head=KVC_AGG_MEAN, add_head_mean=1,
                  softmax_scale=0.0, value_norm=0, order=KVC_ORDER_RANK, min_per_layer=0,
-                 unstructured=0, causal_tail=0):
+                 unstructured=0, causal_tail=0, keep_first=0, keep_last=0):
         super().__init__(batch, layers, hq, hkv, head_dim, window, dtype, agg_task, agg_group,
                          agg_head, add_head_mean, softmax_scale, value_norm, order,
-                         min_per_layer, unstructured, causal_tail)
+                         min_per_layer, unstructured, causal_tail, keep_first, keep_last)
 
 
 class _Inputs(C.Structure):

@@ -73,6 +73,9 @@ static kvc_status check_params(const kvc_params* p) {
     set_error("unknown output order %d", p->order); return KVC_ERR_INVALID_ARG;
   }
   if (p->min_per_layer < 0) { set_error("min_per_layer must be >= 0"); return KVC_ERR_INVALID_ARG; }
+  if (p->keep_first < 0 || p->keep_last < 0) {
+    set_error("keep_first and keep_last must be >= 0"); return KVC_ERR_INVALID_ARG;
+  }
   if (p->batch > KVC_MAX_BATCH) {
     set_error("batch %d exceeds KVC_MAX_BATCH", p->batch); return KVC_ERR_UNSUPPORTED;
   }
@@ -117,6 +120,7 @@ static kvc_status make_problem(const kvc_params* p, const int64_t* cu, Problem* 
   pb->agg_head = p->agg_head; pb->add_head_mean = p->add_head_mean;
   pb->value_norm = p->value_norm; pb->order = p->order; pb->min_per_layer = p->min_per_layer;
   pb->unstructured = p->unstructured; pb->causal_tail = p->causal_tail;
+  pb->keep_first = p->keep_first; pb->keep_last = p->keep_last;
   pb->sel_rows = p->unstructured ? p->layers * p->hkv : p->layers;
   pb->scale = p->softmax_scale > 0.0f ? p->softmax_scale
                                       : 1.0f / std::sqrt(float(p->head_dim));

@@ -22,7 +22,7 @@ struct PtrTable {
 struct Problem {
   int32_t batch, layers, hq, hkv, group, d, window, dtype;
   int32_t agg_task, agg_group, agg_head, add_head_mean;
-  int32_t value_norm, order, min_per_layer, unstructured, causal_tail;
+  int32_t value_norm, order, min_per_layer, unstructured, causal_tail, keep_first, keep_last;
   int32_t sel_rows;   // rows of the selection pool per sequence: layers, or layers*hkv
   float scale;        // softmax scale actually used
   int64_t total;      // T

@@ -237,6 +237,7 @@ __global__ __launch_bounds__(256) void score_merge(SeqTable seq, int rows_per_se
 // ---------------------------------------------------------------------------
 struct FinishArgs {
   int row_chunks, hkv, total, group_max, add_head_mean, chunks_per_head, task_max;
+  int keep_first, keep_last;   // forced retention: these tokens of every sequence score +inf
   float group_norm, inv_window;
 };
 
@@ -267,13 +268,22 @@ __device__ __forceinline__ float finish_group_value(const float* part, const Fin
   return v;
 }
 
-__global__ void score_finish(const float* part, FinishArgs a, float* S, size_t layer_stride,
-                             const float* __restrict__ vnorm) {
+__global__ void score_finish(const float* part, FinishArgs a, SeqTable seq, float* S,
+                             size_t layer_stride, const float* __restrict__ vnorm) {
   const int c = blockIdx.x * blockDim.x + threadIdx.x;
   const int hkv = a.hkv, total = a.total, add_head_mean = a.add_head_mean;
   if (c >= total) return;
   part += blockIdx.y * layer_stride;
   S += blockIdx.y * layer_stride;
+  if (a.keep_first > 0 || a.keep_last > 0) {
+    int b = 0;
+    while (b + 1 < seq.batch && seq.cu[b + 1] <= c) ++b;          // sequence of token c
+    const int pos = c - seq.cu[b], n = seq.cu[b + 1] - seq.cu[b];
+    if (pos < a.keep_first || pos >= n - a.keep_last) {
+      for (int h = 0; h < hkv; ++h) S[(size_t)h * total + c] = __builtin_inff();
+      return;
+    }
+  }
   float sum = 0.f;
   float vals[8];
   for (int h0 = 0; h0 < hkv; h0 += 8) {
@@ -386,6 +396,7 @@ kvc_status launch_score(const Problem& pb, const void* const* q, const void* con
   fa.chunks_per_head = (mfma_supported(pb) && pb.window > MF_RCHUNK) ? pb.window / MF_RCHUNK : 1;
   fa.group_norm = fa.group_max ? 1.f : 1.f / float(pb.group);
   fa.inv_window = 1.f / float(pb.window);
+  fa.keep_first = pb.keep_first; fa.keep_last = pb.keep_last;
   const float c2 = pb.scale * LOG2E;
   const int total = int(pb.total);
   const int task_max = pb.agg_task == KVC_AGG_MAX, group_max = pb.agg_group == KVC_AGG_MAX;
@@ -465,12 +476,12 @@ kvc_status launch_score(const Problem& pb, const void* const* q, const void* con
     }
     if (per_layer_finish)
       KVC_LAUNCH("score_finish", stream, score_finish<<<(total + 255) / 256, 256, 0, stream>>>(
-          part, fa, S_l, 0, vnorm));
+          part, fa, pb.seq, S_l, 0, vnorm));
   }
   // emitted in place: one launch finishes every layer
   if (!per_layer_finish && pb.layers > 0 && total > 0)
     KVC_LAUNCH("score_finish", stream, score_finish<<<dim3((total + 255) / 256, pb.layers), 256, 0, stream>>>(
-        S, fa, S, size_t(pb.hkv) * total, nullptr));
+        S, fa, pb.seq, S, size_t(pb.hkv) * total, nullptr));
   return KVC_OK;
 }
 

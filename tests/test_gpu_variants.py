@@ -392,3 +392,41 @@ def test_compress_causal_tail_end_to_end():
     tau = ref["tau"]
     for l in range(cfg.layers):
         assert int((ref["I"][l] > tau * (1 + EPS)).sum()) <= int(lens[l]) <= int((ref["I"][l] >= tau * (1 - EPS)).sum())
+
+
+# ------------------------------------------------------------ forced retention
+@pytest.mark.parametrize("cid,over,kf,kl", [(1, dict(layers=3, n=2000), 4, 64),
+                                             (3, dict(layers=2, batch=3, n_range=(300, 1500)), 2, 10),
+                                             (1, dict(layers=2, n=900, hq=24, hkv=12), 3, 0)])
+def test_compress_forced_retention(cid, over, kf, kl):
+    _say(f"forced retention cfg={cid} first={kf} last={kl}")
+    cfg = wl.get_config(cid, **over)
+    w = Workload(cfg)
+    dw = DeviceWorkload(w)
+    got = _run_variant(w, dw, keep_first=kf, keep_last=kl)
+    ref = w.oracle(keep_first=kf, keep_last=kl)
+    c = cfg
+    for b in range(c.batch):
+        lo, hi = int(w.cu[b]), int(w.cu[b + 1])
+        n = hi - lo
+        forced = list(range(min(kf, n))) + list(range(max(n - kl, min(kf, n)), n))
+        r = ref[b]
+        S_g = got["S"][:, :, lo:hi]
+        finite = np.isfinite(r["S"])
+        assert np.array_equal(np.isinf(S_g), ~finite)
+        np.testing.assert_allclose(S_g[finite], r["S"][finite], rtol=EPS)
+        lens = got["lengths"][b]
+        assert int(lens.sum()) == w.budgets[b] and int(lens.min()) >= len(forced)
+        for l in range(c.layers):
+            for h in range(c.hkv):
+                assert got["idx"][l, h, lo:lo + len(forced)].tolist() == forced
+            nl = int(lens[l])
+            base = int(got["offsets"][b * c.layers + l]) * c.hkv * c.head_dim
+            kblk = got["k_out"][base: base + c.hkv * nl * c.head_dim].reshape(c.hkv, nl, c.head_dim)
+            for h in range(c.hkv):
+                np.testing.assert_array_equal(kblk[h], w.seq[b][l][1][h, got["idx"][l, h, lo:lo + nl]])
+            tau = r["tau"]
+            if np.isfinite(tau):
+                lo_ok = int((r["I"][l] > tau * (1 + EPS)).sum())
+                hi_ok = int((r["I"][l] >= tau * (1 - EPS)).sum())
+                assert lo_ok <= nl <= hi_ok

@@ -229,3 +229,36 @@ def test_causal_tail_rows_are_softmaxes_over_their_visible_prefix():
     np.testing.assert_allclose(orc.attention(q[:1], k, 0.3, causal_tail=True), orc.attention(q[:1], k, 0.3), rtol=1e-14)
     with pytest.raises(ValueError):
         orc.attention(q, k[:4], 0.3, causal_tail=True)
+
+
+# ------------------------------------------------------------ forced retention
+def test_force_keep_marks_exactly_the_named_tokens():
+    s = np.arange(12.0).reshape(2, 6)
+    out = orc.force_keep(s, 2, 1)
+    assert np.isinf(out[:, [0, 1, 5]]).all() and np.array_equal(out[:, 2:5], s[:, 2:5])
+    assert orc.force_keep(s, 0, 0) is s
+    assert np.isinf(orc.force_keep(s, 4, 4)).all()            # overlapping ranges cover everything
+    with pytest.raises(ValueError):
+        orc.force_keep(s, -1, 0)
+
+
+def test_forced_tokens_are_retained_in_every_head_and_come_first():
+    rng = np.random.default_rng(13)
+    lyr, hq, hkv, n, m, d = 3, 4, 2, 20, 3, 8
+    q = [rng.standard_normal((hq, m, d)).astype(np.float32) for _ in range(lyr)]
+    k = [rng.standard_normal((hkv, n, d)).astype(np.float32) for _ in range(lyr)]
+    v = [rng.standard_normal((hkv, n, d)).astype(np.float32) for _ in range(lyr)]
+    forced = [0, 1, 17, 18, 19]
+    budget = lyr * len(forced) + 4
+    out = orc.compress(q, k, v, budget, keep_first=2, keep_last=3)
+    plain = orc.compress(q, k, v, budget)
+    assert int(out["lengths"].sum()) == budget and int(out["lengths"].min()) >= len(forced)
+    for l in range(lyr):
+        for h in range(hkv):
+            assert out["idx"][l, h, :len(forced)].tolist() == forced      # +inf ties: ascending position
+            # the others keep the order they have without forcing
+            rest = [c for c in plain["idx"][l, h].tolist() if c not in forced]
+            assert out["idx"][l, h, len(forced):].tolist() == rest
+    # with exactly Lyr * forced slots every layer keeps the forced tokens and nothing else
+    tight = orc.compress(q, k, v, lyr * len(forced), keep_first=2, keep_last=3)
+    assert tight["lengths"].tolist() == [len(forced)] * lyr
