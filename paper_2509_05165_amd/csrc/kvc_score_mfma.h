@@ -74,22 +74,36 @@ __device__ __forceinline__ void stats_fold(const f32x16& acc, float c2, float& m
 // The same fold for two tiles (x0, x1), cut into 16 slices so that slice i can be
 // issued right behind MFMA i of the next tile.  Slices 0-1: tile maxima; slice
 // 2: new running maxima and rescale; slices 3-15: the 32 exponentials.
+//
+// track == false (wave-uniform) freezes the reference: 2^(t - mrun) is summed
+// with mrun as it stands, no maxima, no rescale.  Any reference within about
+// +-100 of the true maximum (log2 units) gives the same sum to fp32 precision;
+// a logit more than 127 above it overflows the sum to inf, which the caller
+// detects and answers by running the chunk again with tracking on.
 struct StatsCarry { float amax[2], nmn[2], s[2], e[3]; int eb[3]; };
 __device__ __forceinline__ void stats_slice(int i, const f32x16& x0, const f32x16& x1, float c2,
-                                            float (&mrun)[2], float (&srun)[2], StatsCarry& c) {
+                                            float (&mrun)[2], float (&srun)[2], StatsCarry& c,
+                                            bool track) {
   if (i < 2) {
-    const f32x16& x = i ? x1 : x0;
-    float m = fmaxf(x[0], x[1]);
+    if (track) {
+      const f32x16& x = i ? x1 : x0;
+      float m = fmaxf(x[0], x[1]);
 #pragma unroll
-    for (int r = 2; r < 16; r += 2) m = fmaxf(m, fmaxf(x[r], x[r + 1]));
-    c.amax[i] = m;
+      for (int r = 2; r < 16; r += 2) m = fmaxf(m, fmaxf(x[r], x[r + 1]));
+      c.amax[i] = m;
+    }
   } else if (i == 2) {
+    if (track) {
 #pragma unroll
-    for (int b = 0; b < 2; ++b) {
-      const float mn = fmaxf(mrun[b], c.amax[b] * c2);
-      c.s[b] = srun[b] * fast_exp2(mrun[b] - mn);
-      c.nmn[b] = -mn;
-      mrun[b] = mn;
+      for (int b = 0; b < 2; ++b) {
+        const float mn = fmaxf(mrun[b], c.amax[b] * c2);
+        c.s[b] = srun[b] * fast_exp2(mrun[b] - mn);
+        c.nmn[b] = -mn;
+        mrun[b] = mn;
+      }
+    } else {
+#pragma unroll
+      for (int b = 0; b < 2; ++b) { c.s[b] = srun[b]; c.nmn[b] = -mrun[b]; }
     }
   } else {
     // elements 0..31 (tile 0 then tile 1): slices 3..8 take three, 9..15 take two.
@@ -409,6 +423,12 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
     }
   };
 
+  // STATS runs the chunk with the reference frozen after 256 keys; if a sum
+  // overflowed (a later logit more than 2^127 above the reference: never seen on
+  // attention-like data, possible on adversarial input) the whole workgroup runs
+  // the chunk once more with the maxima tracked throughout.
+  bool track_all = false;
+  for (;;) {
   // Tile 0 has landed (and the query fragments); tile 1 is requested only now, so
   // that at kernel start, when every workgroup asks at once, all first tiles are
   // served before any second one.
@@ -446,6 +466,9 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
     for (int it = 0; it < npipe; ++it) {
       if ((it + prio_phase) & 1) __builtin_amdgcn_s_setprio(1);
       else __builtin_amdgcn_s_setprio(0);
+      // STATS: the running maxima are taken from the first two macro tiles (256 keys)
+      // and then frozen as the reference of the sums (see stats_slice)
+      const bool track = track_all || it < 2;
       const unsigned char* kb = kbuf[it & 1];
 #pragma unroll
       for (int j = 0; j < NT; ++j) {
@@ -477,11 +500,11 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
             acc[p][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr, as_bf16x8(qf[qb][ks]), cin, 0, 0, 0);
           if (qb == 1) kf[ks] = *reinterpret_cast<const uint4*>(nkb + (fbase ^ (32 * ks)));
           if (!EMIT) {
-            stats_slice(i, acc[p ^ 1][0], acc[p ^ 1][1], c2, mrun, srun, carry);
+            stats_slice(i, acc[p ^ 1][0], acc[p ^ 1][1], c2, mrun, srun, carry, track);
             // The slice results feed nothing until the end of the tile, so without an
             // anchor the optimiser sinks the whole slice past the tile barrier (all
             // vector work of a tile would then run after its MFMAs, not beside them).
-            if (i < 2) asm volatile("" : "+v"(carry.amax[i]));
+            if (i < 2) { if (track) asm volatile("" : "+v"(carry.amax[i])); }
             else if (i == 2) asm volatile("" : "+v"(carry.s[0]), "+v"(carry.s[1]), "+v"(carry.nmn[0]), "+v"(carry.nmn[1]));
             else asm volatile("" : "+v"(carry.s[0]), "+v"(carry.s[1]), "+v"(carry.e[0]), "+v"(carry.e[1]));
           } else {
@@ -519,6 +542,16 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
   }
   __syncthreads();
   if (EMIT && ntiles > 0) epilogue(ntiles - 1, tail > 0 ? tail : MF_TILE);
+  if (EMIT || track_all) break;
+  const int overflowed = !(srun[0] < 3.0e38f) || !(srun[1] < 3.0e38f);   // inf or NaN
+  if (!__syncthreads_or(overflowed)) break;
+  track_all = true;
+  mrun[0] = mrun[1] = NEG_BIG;
+  srun[0] = srun[1] = 0.f;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) { acc[1][0][r] = ninf; acc[1][1][r] = ninf; }
+  issue_tile(0);
+  }
 
   if (!EMIT) {
     // lanes l and l+32 hold the same query over different keys

@@ -329,3 +329,38 @@ def test_copy_probe_copies():
     assert torch.equal(src, dst)
     with pytest.raises(kv.KvcError):
         kv.kvc_copy_probe(dst.data_ptr(), src.data_ptr(), 10, stream())
+
+
+# ------------------------------------------------------------------ frozen softmax reference
+@pytest.mark.parametrize("kind", ["late-spike", "early-spike", "late-spike-moderate"])
+def test_score_stats_reference_overflow_rerun(kind):
+    """The stats pass freezes its reference after the first 256 keys of a chunk.
+    Keys far above it later in the chunk overflow the sum and must trigger the
+    tracked rerun; keys far above everything at the start must not lose the rest."""
+    _say(f"stats reference {kind}")
+    cfg = wl.get_config(1, layers=1, n=5000)
+    w = Workload(cfg)
+    k = (w.k[0].astype(np.uint32) << 16).view(np.float32).copy()       # [hkv, n, d]
+    q = (w.q[0][0].astype(np.uint32) << 16).view(np.float32)            # [hq, M, d]
+    u = q.reshape(cfg.hkv, -1, cfg.head_dim).mean(axis=1)
+    u /= np.linalg.norm(u, axis=1, keepdims=True)
+    # logit lift of about +/-scale*|u.q| per unit: 300 sigma along the mean query direction
+    # is > 127 log2 units for most rows, 40 sigma stays inside the fp32 range
+    amp = {"late-spike": 3000.0, "early-spike": 3000.0, "late-spike-moderate": 400.0}[kind]
+    where = {"late-spike": [1500, 4100], "early-spike": [3], "late-spike-moderate": [1500, 4100]}[kind]
+    for c in where:
+        k[:, c, :] += amp * u
+    kb = wl.f32_to_bf16_bits(k)
+    w.k[0] = kb
+    w.seq[0][0] = (w.seq[0][0][0], kb, w.seq[0][0][2])
+    dw = DeviceWorkload(w)
+    S = torch.zeros((1, cfg.hkv, w.total), dtype=torch.float32, device="cuda")
+    kv.kvc_score(w.params(), dw.ptrs(dw.q), dw.ptrs(dw.k), w.cu, S.data_ptr(), dw.ws.data_ptr(),
+                 dw.ws_bytes, stream())
+    torch.cuda.synchronize()
+    got = S.cpu().numpy()[0]
+    ref = orc.score_layer(orc.widen(w.seq[0][0][0]), orc.widen(kb))
+    assert np.isfinite(got).all()
+    big = ref > 1e-30                       # where the oracle's own float64 value is not denormal dust
+    np.testing.assert_allclose(got[big], ref[big], rtol=1e-4)
+    assert np.all(got[~big] <= 1e-29)
