@@ -22,7 +22,7 @@ import numpy as np  # noqa: E402
 METRIC = "context tokens compressed/sec at Llama-3-8B shape, L=128k"
 PEAK_BF16_MFMA_TFLOPS = 2500.0
 PEAK_HBM_GBPS = 8000.0
-# HBM bytes per launch of the score kernels at the config-2 layer shape (32/8 heads, d=128,
+# HBM bytes per layer of the score kernels at the config-2 layer shape (32/8 heads, d=128,
 # N=131072, M=64), from rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by the copy-probe factors
 # (2.000 / 1.000); source: profiles/score_mfma_config2_hbm_traffic.md
 MEASURED_TRAFFIC_BYTES = {"score_mfma<stats>": 273.9e6, "score_mfma<emit>": 279.2e6}
@@ -183,21 +183,24 @@ def main():
     for name, (c, ms) in sorted(per_step.items(), key=lambda x: -x[1][1]):
         log(f"  {name:28s} launches/step={c:4d}  ms/step={ms:8.3f}  avg_us={1e3 * ms / max(c, 1):9.1f}")
 
-    # dominant kernel: the score contraction (one launch = one layer's
-    # window-Q x K^T over all heads and tokens)
+    # dominant kernel: the score contraction (one launch = window-Q x K^T of
+    # cfg.layers / launches-per-step layers over all heads and tokens)
     dom = max(per_step.items(), key=lambda x: x[1][1])[0]
     roofline = None
     if dom.startswith("score_mfma"):
-        flops_per_launch = 2.0 * cfg.hq * cfg.window * cfg.head_dim * total   # one layer
         c, ms = per_step[dom]
+        layers_per_launch = cfg.layers / c
+        flops_per_launch = 2.0 * cfg.hq * cfg.window * cfg.head_dim * total * layers_per_launch
         avg_s = ms / c * 1e-3
         achieved = flops_per_launch / avg_s / 1e12
         layer_shape = (cfg.hq, cfg.hkv, cfg.head_dim, cfg.window, total) == (32, 8, 128, 64, 131072)
         roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved,
                     "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
                     "frac": achieved / PEAK_BF16_MFMA_TFLOPS,
-                    "traffic": MEASURED_TRAFFIC_BYTES.get(dom) if layer_shape else None,
-                    "avg_launch_us": avg_s * 1e6, "launches_per_step": c}
+                    "traffic": (MEASURED_TRAFFIC_BYTES[dom] * layers_per_launch
+                                if layer_shape and dom in MEASURED_TRAFFIC_BYTES else None),
+                    "avg_launch_us": avg_s * 1e6, "launches_per_step": c,
+                    "layers_per_launch": layers_per_launch}
     stages = {
         "score_ms": sum(ms for k, (c, ms) in per_step.items() if k.startswith("score")),
         "rank_ms": sum(ms for k, (c, ms) in per_step.items() if k.startswith("head_rank")),

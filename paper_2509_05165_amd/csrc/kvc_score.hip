@@ -182,18 +182,20 @@ __global__ __launch_bounds__(256) void score_emit_generic(
 // ---------------------------------------------------------------------------
 constexpr int MERGE_ROWS = 16;
 
-__global__ __launch_bounds__(256) void score_merge(SeqTable seq, int rows_per_seq, int chunk_keys,
+__global__ __launch_bounds__(256) void score_merge(SeqTable seq, int rows_per_seq, int layers,
+                                                   int chunk_keys,
                                                    const float* __restrict__ part_m,
                                                    const float* __restrict__ part_s,
                                                    float* __restrict__ lse2) {
   __shared__ float sm[16][MERGE_ROWS], ss[16][MERGE_ROWS];
   const int r = threadIdx.x & (MERGE_ROWS - 1), cg = threadIdx.x >> 4;
-  const int rows = rows_per_seq * seq.batch;
+  // rows of every layer of the launch: row = (layer * batch + sequence) * rows_per_seq + ...
+  const int rows = rows_per_seq * seq.batch * layers;
   const int row = blockIdx.x * MERGE_ROWS + r;
   float mm = NEG_BIG, acc = 0.f;
   int chunks = 0;
   if (row < rows) {
-    const int b = row / rows_per_seq;
+    const int b = (row / rows_per_seq) % seq.batch;
     const int n = seq.cu[b + 1] - seq.cu[b];
     chunks = (n + chunk_keys - 1) / chunk_keys;
     for (int c = cg; c < chunks; c += 16) {
@@ -269,11 +271,12 @@ __device__ __forceinline__ float finish_group_value(const float* part, const Fin
 }
 
 __global__ void score_finish(const float* part, FinishArgs a, SeqTable seq, float* S,
-                             size_t layer_stride, const float* __restrict__ vnorm) {
+                             size_t part_layer_stride, size_t layer_stride,
+                             const float* __restrict__ vnorm) {
   const int c = blockIdx.x * blockDim.x + threadIdx.x;
   const int hkv = a.hkv, total = a.total, add_head_mean = a.add_head_mean;
   if (c >= total) return;
-  part += blockIdx.y * layer_stride;
+  part += blockIdx.y * part_layer_stride;
   S += blockIdx.y * layer_stride;
   if (a.keep_first > 0 || a.keep_last > 0) {
     int b = 0;
@@ -345,12 +348,21 @@ __global__ __launch_bounds__(256) void value_norm_kernel(const T* __restrict__ v
 
 
 constexpr int GEN_CHUNK = 256;
-constexpr int MF_CHUNK = 2048;
+constexpr int MF_CHUNK = 2048;        // keys per workgroup of the matrix-core path ...
+constexpr int MF_CHUNK_BIG = 4096;    // ... or twice that when the launch still has plenty of workgroups
+
+// A workgroup pays a fixed price (query fragments, first tile) per chunk, so
+// longer chunks are better as long as the compute units stay oversubscribed.
+inline int mfma_chunk(const Problem& pb, int row_chunks) {
+  const int64_t big_chunks = (pb.max_seqlen + MF_CHUNK_BIG - 1) / MF_CHUNK_BIG;
+  const int64_t wgs = big_chunks * pb.hkv * row_chunks * pb.batch * pb.layers;
+  return wgs >= 2048 ? MF_CHUNK_BIG : MF_CHUNK;
+}
 constexpr int MIN_CHUNK = 256;   // workspace is sized for the smallest chunk in use
 
 struct ScoreLayout {
-  size_t off_m, off_s, off_lse, off_part, off_vnorm, total;
-  int max_chunks, rows_layer, row_chunks;
+  size_t off_m, off_s, off_lse, off_part, off_vnorm, total, part_layer;
+  int max_chunks, rows_layer, row_chunks, layers_held;
 };
 
 ScoreLayout score_layout(const Problem& pb) {
@@ -358,16 +370,22 @@ ScoreLayout score_layout(const Problem& pb) {
   L.rows_layer = pb.batch * pb.hq * pb.window;
   L.max_chunks = int((pb.max_seqlen + MIN_CHUNK - 1) / MIN_CHUNK);
   if (L.max_chunks < 1) L.max_chunks = 1;
-  L.row_chunks = mfma_supported(pb) ? (pb.group * pb.window + MF_RCHUNK - 1) / MF_RCHUNK : 1;
+  const bool mfma = mfma_supported(pb);
+  L.row_chunks = mfma ? (pb.group * pb.window + MF_RCHUNK - 1) / MF_RCHUNK : 1;
+  // the matrix-core path runs all layers in one launch and keeps the statistics,
+  // log-sum-exps and group partials of every layer; the generic path goes layer by layer
+  L.layers_held = mfma ? pb.layers : 1;
+  if (mfma) L.max_chunks = int((pb.max_seqlen + MF_CHUNK - 1) / MF_CHUNK) > 0
+                               ? int((pb.max_seqlen + MF_CHUNK - 1) / MF_CHUNK) : 1;
   size_t cur = 0;
-  L.off_m = cur;    cur += align_up(size_t(L.rows_layer) * L.max_chunks * 4);
-  L.off_s = cur;    cur += align_up(size_t(L.rows_layer) * L.max_chunks * 4);
-  L.off_lse = cur;  cur += align_up(size_t(L.rows_layer) * 4);
+  L.off_m = cur;    cur += align_up(size_t(L.rows_layer) * L.layers_held * L.max_chunks * 4);
+  L.off_s = cur;    cur += align_up(size_t(L.rows_layer) * L.layers_held * L.max_chunks * 4);
+  L.off_lse = cur;  cur += align_up(size_t(L.rows_layer) * L.layers_held * 4);
   L.off_part = cur;
   // partials are needed when row chunks must be combined, or when more than 8
   // KV heads make the in-place finish impossible
-  if (L.row_chunks > 1 || pb.hkv > 8)
-    cur += align_up(size_t(L.row_chunks) * pb.hkv * size_t(pb.total) * 4);
+  L.part_layer = size_t(L.row_chunks) * pb.hkv * size_t(pb.total);
+  if (L.row_chunks > 1 || pb.hkv > 8) cur += align_up(L.part_layer * L.layers_held * 4);
   L.off_vnorm = cur;
   if (pb.value_norm) cur += align_up(size_t(pb.hkv) * size_t(pb.total) * 4);   // one layer's weights
   L.total = cur;
@@ -401,39 +419,62 @@ kvc_status launch_score(const Problem& pb, const void* const* q, const void* con
   const int total = int(pb.total);
   const int task_max = pb.agg_task == KVC_AGG_MAX, group_max = pb.agg_group == KVC_AGG_MAX;
   const bool mfma = mfma_supported(pb);
-  const int chunk = mfma ? MF_CHUNK : GEN_CHUNK;
+  const int chunk = mfma ? mfma_chunk(pb, L.row_chunks) : GEN_CHUNK;
   const int chunks = int((pb.max_seqlen + chunk - 1) / chunk);
   const int rows_per_seq = pb.hq * pb.window;
 
-  for (int l = 0; l < pb.layers; ++l) {
-    float* S_l = S + size_t(l) * pb.hkv * total;
-    float* part = separate ? reinterpret_cast<float*>(w + L.off_part) : S_l;
-    if (mfma) {
-      const uint16_t* ql = static_cast<const uint16_t*>(q[l]);
-      const uint16_t* kl = static_cast<const uint16_t*>(k[l]);
-      dim3 grid(chunks, pb.hkv * L.row_chunks, pb.batch);
-      const int nqb0 = (pb.group * pb.window < MF_RCHUNK ? pb.group * pb.window : MF_RCHUNK) / 32;
+  if (mfma) {
+    // One launch per pass for all layers (blockIdx.z = layer * batch + sequence).
+    PtrTable qt{}, kt{};
+    for (int l = 0; l < pb.layers; ++l) { qt.p[l] = q[l]; kt.p[l] = k[l]; }
+    float* part_all = separate ? reinterpret_cast<float*>(w + L.off_part) : S;
+    const size_t out_stride = separate ? L.part_layer : size_t(pb.hkv) * total;
+    dim3 grid(chunks, pb.hkv * L.row_chunks, pb.batch * pb.layers);
+    const int nqb0 = (pb.group * pb.window < MF_RCHUNK ? pb.group * pb.window : MF_RCHUNK) / 32;
+    const int rows_all = L.rows_layer * pb.layers;
 #define KVC_SCORE_MFMA(NAME, EMIT, TMAX, WQ, PM, PS, LSE, OUT)                                   \
   KVC_LAUNCH(NAME, stream, score_mfma<EMIT, TMAX, WQ><<<grid, MF_THREADS, 0, stream>>>(           \
-      ql, kl, pb.seq, pb.hq, pb.group, pb.window, total, c2, chunk, L.row_chunks,                \
-      PM, PS, LSE, group_max, pb.causal_tail, OUT))
+      qt, kt, pb.batch, out_stride, pb.seq, pb.hq, pb.group, pb.window, total, c2, chunk,        \
+      L.row_chunks, PM, PS, LSE, group_max, pb.causal_tail, OUT))
 #define KVC_SCORE_MFMA_WQ(NAME, EMIT, TMAX, PM, PS, LSE, OUT)                     \
   do {                                                                            \
     if (nqb0 <= 2) { KVC_SCORE_MFMA(NAME, EMIT, TMAX, 1, PM, PS, LSE, OUT); }       \
     else if (nqb0 <= 4) { KVC_SCORE_MFMA(NAME, EMIT, TMAX, 2, PM, PS, LSE, OUT); }  \
     else { KVC_SCORE_MFMA(NAME, EMIT, TMAX, 4, PM, PS, LSE, OUT); }                 \
   } while (0)
+    if (chunks > 0) {
       KVC_SCORE_MFMA_WQ("score_mfma<stats>", false, true, part_m, part_s, nullptr, nullptr);
-      KVC_LAUNCH("score_merge", stream, score_merge<<<(L.rows_layer + MERGE_ROWS - 1) / MERGE_ROWS, 256, 0, stream>>>(
-          pb.seq, rows_per_seq, chunk, part_m, part_s, lse2));
+      KVC_LAUNCH("score_merge", stream, score_merge<<<(rows_all + MERGE_ROWS - 1) / MERGE_ROWS, 256, 0, stream>>>(
+          pb.seq, rows_per_seq, pb.layers, chunk, part_m, part_s, lse2));
       if (task_max) {
-        KVC_SCORE_MFMA_WQ("score_mfma<emit>", true, true, nullptr, nullptr, lse2, part);
+        KVC_SCORE_MFMA_WQ("score_mfma<emit>", true, true, nullptr, nullptr, lse2, part_all);
       } else {
-        KVC_SCORE_MFMA_WQ("score_mfma<emit>", true, false, nullptr, nullptr, lse2, part);
+        KVC_SCORE_MFMA_WQ("score_mfma<emit>", true, false, nullptr, nullptr, lse2, part_all);
       }
+    }
 #undef KVC_SCORE_MFMA_WQ
 #undef KVC_SCORE_MFMA
-    } else {
+    if (vnorm) {   // one buffer of value norms: layer by layer
+      for (int l = 0; l < pb.layers; ++l) {
+        const size_t rows = size_t(pb.hkv) * total;
+        const unsigned blocks = unsigned((rows * 16 + 255) / 256);
+        KVC_LAUNCH("value_norm_kernel", stream, value_norm_kernel<uint16_t><<<blocks, 256, 0, stream>>>(
+            static_cast<const uint16_t*>(v[l]), rows, pb.d, vnorm));
+        KVC_LAUNCH("score_finish", stream, score_finish<<<(total + 255) / 256, 256, 0, stream>>>(
+            part_all + size_t(l) * out_stride, fa, pb.seq, S + size_t(l) * pb.hkv * total, 0, 0, vnorm));
+      }
+    } else if (pb.layers > 0 && total > 0) {
+      KVC_LAUNCH("score_finish", stream, score_finish<<<dim3((total + 255) / 256, pb.layers), 256, 0, stream>>>(
+          part_all, fa, pb.seq, S, out_stride, size_t(pb.hkv) * total, nullptr));
+    }
+    return KVC_OK;
+  }
+
+  // generic fp32 path: layer by layer
+  for (int l = 0; l < pb.layers; ++l) {
+    float* S_l = S + size_t(l) * pb.hkv * total;
+    float* part = separate ? reinterpret_cast<float*>(w + L.off_part) : S_l;
+    {
       const int row_blocks = (pb.window + GEN_RB - 1) / GEN_RB;
       dim3 gs(chunks, pb.hq * row_blocks, pb.batch), ge(chunks, pb.hkv, pb.batch);
       const size_t lds_s = size_t(GEN_TILE) * (pb.d + 1) * 4;
@@ -445,7 +486,7 @@ kvc_status launch_score(const Problem& pb, const void* const* q, const void* con
             ql, kl, pb.seq, pb.hq, pb.group, pb.window, pb.d, total, c2, chunk, L.max_chunks,
             pb.causal_tail, part_m, part_s));
         KVC_LAUNCH("score_merge", stream, score_merge<<<(L.rows_layer + MERGE_ROWS - 1) / MERGE_ROWS, 256, 0, stream>>>(
-            pb.seq, rows_per_seq, chunk, part_m, part_s, lse2));
+            pb.seq, rows_per_seq, 1, chunk, part_m, part_s, lse2));
         KVC_LAUNCH("score_emit_generic", stream, score_emit_generic<uint16_t><<<ge, 256, lds_e, stream>>>(
             ql, kl, pb.seq, pb.hq, pb.group, pb.window, pb.d, total, c2, chunk, lse2, task_max,
             group_max, pb.causal_tail, part));
@@ -456,7 +497,7 @@ kvc_status launch_score(const Problem& pb, const void* const* q, const void* con
             ql, kl, pb.seq, pb.hq, pb.group, pb.window, pb.d, total, c2, chunk, L.max_chunks,
             pb.causal_tail, part_m, part_s));
         KVC_LAUNCH("score_merge", stream, score_merge<<<(L.rows_layer + MERGE_ROWS - 1) / MERGE_ROWS, 256, 0, stream>>>(
-            pb.seq, rows_per_seq, chunk, part_m, part_s, lse2));
+            pb.seq, rows_per_seq, 1, chunk, part_m, part_s, lse2));
         KVC_LAUNCH("score_emit_generic", stream, score_emit_generic<float><<<ge, 256, lds_e, stream>>>(
             ql, kl, pb.seq, pb.hq, pb.group, pb.window, pb.d, total, c2, chunk, lse2, task_max,
             group_max, pb.causal_tail, part));
@@ -476,12 +517,12 @@ kvc_status launch_score(const Problem& pb, const void* const* q, const void* con
     }
     if (per_layer_finish)
       KVC_LAUNCH("score_finish", stream, score_finish<<<(total + 255) / 256, 256, 0, stream>>>(
-          part, fa, pb.seq, S_l, 0, vnorm));
+          part, fa, pb.seq, S_l, 0, 0, vnorm));
   }
   // emitted in place: one launch finishes every layer
   if (!per_layer_finish && pb.layers > 0 && total > 0)
     KVC_LAUNCH("score_finish", stream, score_finish<<<dim3((total + 255) / 256, pb.layers), 256, 0, stream>>>(
-        S, fa, pb.seq, S, size_t(pb.hkv) * total, nullptr));
+        S, fa, pb.seq, S, size_t(pb.hkv) * total, size_t(pb.hkv) * total, nullptr));
   return KVC_OK;
 }
 

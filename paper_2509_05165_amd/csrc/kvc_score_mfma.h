@@ -164,7 +164,7 @@ __device__ __forceinline__ void lds_dma16_s(const void* sbase, uint32_t voff, ui
                : "memory");
 }
 
-// grid: (chunks, Hkv * row_chunks, Bt), 256 threads.  WQ = waves along the query
+// grid: (chunks, Hkv * row_chunks, Lyr * Bt), 256 threads.  WQ = waves along the query
 // rows (each owns 2 blocks of 32 rows); the other 4/WQ waves split the key tiles.
 //
 // Schedule of one workgroup over its macro tiles (two K buffers, tile t in
@@ -183,7 +183,7 @@ __device__ __forceinline__ void lds_dma16_s(const void* sbase, uint32_t voff, ui
 // tiles above it are processed one key tile at a time with the mask applied.
 template <bool EMIT, bool TASK_MAX, int WQ>
 __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
-    const uint16_t* __restrict__ q_layer, const uint16_t* __restrict__ k_layer, SeqTable seq,
+    PtrTable q_tab, PtrTable k_tab, int batch, size_t out_layer_stride, SeqTable seq,
     int hq, int group, int window, int total, float c2, int chunk_keys, int row_chunks,
     float* __restrict__ part_m, float* __restrict__ part_s, const float* __restrict__ lse2,
     int group_max, int causal, float* __restrict__ out) {
@@ -195,7 +195,13 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
   __shared__ float stat[EMIT ? 1 : 4][2][32][2];               // STATS: per wave (max, sum)
   __shared__ __attribute__((aligned(16))) float lse_s[EMIT ? MF_RCHUNK : 4];   // EMIT: -lse2 of the row chunk
 
-  const int b = blockIdx.z;
+  // blockIdx.z = layer * batch + sequence: one launch covers every layer, so that
+  // workgroups of the next layer start as those of this one finish and only the
+  // very first ones wait for their first tile with nothing else running
+  const int layer = blockIdx.z / batch, b = blockIdx.z - layer * batch;
+  const uint16_t* __restrict__ q_layer = static_cast<const uint16_t*>(q_tab.p[layer]);
+  const uint16_t* __restrict__ k_layer = static_cast<const uint16_t*>(k_tab.p[layer]);
+  if (EMIT) out += (size_t)layer * out_layer_stride;
   const int tok0 = seq.cu[b], n = seq.cu[b + 1] - tok0;
   const int key_begin = blockIdx.x * chunk_keys;
   if (key_begin >= n) return;
@@ -266,7 +272,7 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
   // EMIT: minus lse2 of this row chunk goes through LDS (one coalesced load)
   float my_nl = 0.f;
   if (EMIT && (int)threadIdx.x < nqb * 32)
-    my_nl = -lse2[((size_t)b * hq + h * group) * window + row0 + threadIdx.x];
+    my_nl = -lse2[((size_t)blockIdx.z * hq + h * group) * window + row0 + threadIdx.x];
   float nl[2][16];   // EMIT: minus lse2 of the lane's accumulator rows, filled after the first barrier
 
   float mrun[2] = {NEG_BIG, NEG_BIG}, srun[2] = {0.f, 0.f};   // STATS, in log2 units
@@ -577,11 +583,12 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
       for (int k2 = 0; k2 < WK; ++k2)
         ss += stat[k2 * WQ + sq][qb][j][1] * fast_exp2(stat[k2 * WQ + sq][qb][j][0] - mm);
       const int r = row0 + blk * 32 + j;
-      const size_t qrow = ((size_t)b * hq + h * group) * window + r;
+      // row index over all layers and sequences of the launch
+      const size_t qrow = ((size_t)blockIdx.z * hq + h * group) * window + r;
       // partial statistics are stored chunk-major so the merge reads coalesced
-      const size_t rows_layer = (size_t)gridDim.z * hq * window;
-      part_m[(size_t)blockIdx.x * rows_layer + qrow] = mm;
-      part_s[(size_t)blockIdx.x * rows_layer + qrow] = ss;
+      const size_t rows_all = (size_t)gridDim.z * hq * window;
+      part_m[(size_t)blockIdx.x * rows_all + qrow] = mm;
+      part_s[(size_t)blockIdx.x * rows_all + qrow] = ss;
     }
   }
 }
