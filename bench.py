@@ -98,7 +98,7 @@ def main():
     ap.add_argument("--n", type=int, default=None, help="override context length (debug)")
     ap.add_argument("--layers", type=int, default=None, help="override layer count (debug)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-layers", type=int, default=3)
+    ap.add_argument("--cpu-layers", type=int, default=8)
     ap.add_argument("--workers", type=int, default=min(16, os.cpu_count() or 1))
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MB",
                     help="only run the library's plain copy kernel on MB MiB (counter calibration)")
