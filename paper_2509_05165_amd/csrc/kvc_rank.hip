@@ -26,6 +26,20 @@ constexpr int RK_BINS = 256;
 __device__ __forceinline__ uint32_t desc_key(float f) { return ~float_to_ordered(f); }
 __device__ __forceinline__ float desc_key_to_float(uint32_t k) { return ordered_to_float(~k); }
 
+// The segment pointers are the same for every lane; telling the compiler so lets
+// it address global memory as scalar base + 32-bit lane offset instead of doing
+// 64-bit vector arithmetic per access.
+template <typename T>
+__device__ __forceinline__ T* uniform_ptr(T* p) {
+  const uint64_t a = reinterpret_cast<uint64_t>(p);
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)a);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(a >> 32));
+  // rebuilt as a global-memory pointer: an integer round trip alone would leave the
+  // compiler with a generic pointer and flat instead of global accesses
+  typedef __attribute__((address_space(1))) T* global_ptr;
+  return (T*)reinterpret_cast<global_ptr>(((uint64_t)hi << 32) | lo);
+}
+
 // Workgroup barrier that orders LDS traffic only: global stores still in flight
 // (the scatter of the previous tile) are not waited for.
 __device__ __forceinline__ void lds_barrier() {
@@ -34,16 +48,20 @@ __device__ __forceinline__ void lds_barrier() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-// lanes (among `valid`) whose 8-bit digit equals mine
+// lanes (among `valid`) whose 8-bit digit equals mine.  Per bit: the lanes that
+// agree with my bit are ~(ballot ^ mine), with `mine` all ones or all zeros;
+// written on 32-bit halves as x & ~(y ^ z), which is one three-input bit
+// operation per half.
 __device__ __forceinline__ uint64_t match_digit(uint32_t digit, uint64_t valid) {
-  uint64_t mask = valid;
+  uint32_t lo = (uint32_t)valid, hi = (uint32_t)(valid >> 32);
 #pragma unroll
   for (int bit = 0; bit < 8; ++bit) {
-    const bool set = (digit >> bit) & 1u;
-    const uint64_t bal = __ballot(set);
-    mask &= set ? bal : ~bal;
+    const uint32_t mine = 0u - ((digit >> bit) & 1u);
+    const uint64_t bal = __ballot(mine != 0u);
+    lo = lo & ~((uint32_t)bal ^ mine);
+    hi = hi & ~((uint32_t)(bal >> 32) ^ mine);
   }
-  return mask;
+  return ((uint64_t)hi << 32) | lo;
 }
 
 __device__ __forceinline__ int lanes_below(uint64_t mask) {
@@ -78,6 +96,8 @@ __device__ __forceinline__ void radix_pass(RankShared& sh, int n, const float* _
                                            float* __restrict__ dst_f) {
   constexpr int shift = PASS * 8;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  src_f = uniform_ptr(src_f); src_k = uniform_ptr(src_k); src_i = uniform_ptr(src_i);
+  dst_k = uniform_ptr(dst_k); dst_i = uniform_ptr(dst_i); dst_f = uniform_ptr(dst_f);
   // exclusive scan of hist[PASS] -> bucket (first 256 threads = 4 waves)
   if (tid < RK_BINS) {
     const uint32_t c = sh.hist[PASS][tid];
@@ -105,8 +125,8 @@ __device__ __forceinline__ void radix_pass(RankShared& sh, int n, const float* _
 #define KVC_RANK_LOAD_TILE(BASE, K, V)                         \
   _Pragma("unroll") for (int e = 0; e < RK_ITEMS; ++e) {       \
     const int pos = (BASE) + woff + e * 64;                    \
-    const int cpos = pos < n ? pos : n - 1;                    \
-    if (PASS == 0) { K[e] = __float_as_uint(src_f[cpos]); V[e] = cpos; } \
+    const uint32_t cpos = uint32_t(pos < n ? pos : n - 1);     /* unsigned: 32-bit offset addressing */ \
+    if (PASS == 0) { K[e] = __float_as_uint(src_f[cpos]); V[e] = int32_t(cpos); } \
     else if (LIN) { K[e] = sh.stage_k[cpos]; V[e] = sh.stage_v[cpos]; }  \
     else { K[e] = src_k[cpos]; V[e] = src_i[cpos]; }           \
   }
