@@ -72,7 +72,7 @@
  * except KVC_ERR_HIP which reports a failed launch (kvc_last_error() has the
  * HIP message).  No function aborts or throws.
  *
- * Limits: Bt <= KVC_MAX_BATCH, Lyr <= KVC_MAX_LAYERS, T < 2^31,
+ * Limits: Bt <= KVC_MAX_BATCH, Lyr <= KVC_MAX_LAYERS, T < 2^30,
  * d * sizeof(element) a multiple of 16 bytes and d <= 256.
  */
 #ifndef KVC_H

@@ -111,8 +111,8 @@ static kvc_status make_problem(const kvc_params* p, const int64_t* cu, Problem* 
     }
     if (n > mx) mx = n;
   }
-  if (cu[p->batch] >= (int64_t(1) << 31)) {
-    set_error("total tokens must be below 2^31"); return KVC_ERR_UNSUPPORTED;
+  if (cu[p->batch] >= (int64_t(1) << 30)) {
+    set_error("total tokens must be below 2^30"); return KVC_ERR_UNSUPPORTED;
   }
   pb->batch = p->batch; pb->layers = p->layers; pb->hq = p->hq; pb->hkv = p->hkv;
   pb->group = p->hq / p->hkv; pb->d = p->head_dim; pb->window = p->window;
@@ -259,8 +259,8 @@ kvc_status kvc_workspace_size(const kvc_params* params, int64_t total_tokens,
   if (st != KVC_OK) return st;
   if (!bytes) { set_error("bytes is NULL"); return KVC_ERR_INVALID_ARG; }
   if (total_tokens < 0 || max_seqlen < 0 || max_seqlen > total_tokens ||
-      total_tokens >= (int64_t(1) << 31)) {
-    set_error("need 0 <= max_seqlen <= total_tokens < 2^31"); return KVC_ERR_INVALID_ARG;
+      total_tokens >= (int64_t(1) << 30)) {
+    set_error("need 0 <= max_seqlen <= total_tokens < 2^30"); return KVC_ERR_INVALID_ARG;
   }
   // A synthetic sequence table with the same totals is enough for sizing.
   Problem pb{};

@@ -40,6 +40,19 @@ __device__ __forceinline__ T* uniform_ptr(T* p) {
   return (T*)reinterpret_cast<global_ptr>(((uint64_t)hi << 32) | lo);
 }
 
+// Element `i` of a 4-byte array through a 32-bit byte offset (the library limits
+// T to 2^30 tokens, so 4*i fits): scalar base + 32-bit lane offset addressing.
+template <typename T>
+__device__ __forceinline__ T& at32(T* base, uint32_t i) {
+  static_assert(sizeof(T) == 4, "4-byte elements");
+  return *reinterpret_cast<T*>(reinterpret_cast<char*>(base) + (i << 2));
+}
+template <typename T>
+__device__ __forceinline__ const T& at32(const T* base, uint32_t i) {
+  static_assert(sizeof(T) == 4, "4-byte elements");
+  return *reinterpret_cast<const T*>(reinterpret_cast<const char*>(base) + (i << 2));
+}
+
 // Workgroup barrier that orders LDS traffic only: global stores still in flight
 // (the scatter of the previous tile) are not waited for.
 __device__ __forceinline__ void lds_barrier() {
@@ -58,8 +71,11 @@ __device__ __forceinline__ uint64_t match_digit(uint32_t digit, uint64_t valid) 
   for (int bit = 0; bit < 8; ++bit) {
     const uint32_t mine = 0u - ((digit >> bit) & 1u);
     const uint64_t bal = __ballot(mine != 0u);
-    lo = lo & ~((uint32_t)bal ^ mine);
-    hi = hi & ~((uint32_t)(bal >> 32) ^ mine);
+    // x & ~(y ^ z) as one v_bitop3_b32 (truth table 0x90: the encoding the compiler
+    // itself picks for that expression; spelled out because it otherwise splits it
+    // into an xor and a shared three-input and)
+    lo = __builtin_amdgcn_bitop3_b32(lo, (uint32_t)bal, mine, 0x90);
+    hi = __builtin_amdgcn_bitop3_b32(hi, (uint32_t)(bal >> 32), mine, 0x90);
   }
   return ((uint64_t)hi << 32) | lo;
 }
@@ -126,9 +142,9 @@ __device__ __forceinline__ void radix_pass(RankShared& sh, int n, const float* _
   _Pragma("unroll") for (int e = 0; e < RK_ITEMS; ++e) {       \
     const int pos = (BASE) + woff + e * 64;                    \
     const uint32_t cpos = uint32_t(pos < n ? pos : n - 1);     /* unsigned: 32-bit offset addressing */ \
-    if (PASS == 0) { K[e] = __float_as_uint(src_f[cpos]); V[e] = int32_t(cpos); } \
+    if (PASS == 0) { K[e] = __float_as_uint(at32(src_f, cpos)); V[e] = int32_t(cpos); } \
     else if (LIN) { K[e] = sh.stage_k[cpos]; V[e] = sh.stage_v[cpos]; }  \
-    else { K[e] = src_k[cpos]; V[e] = src_i[cpos]; }           \
+    else { K[e] = at32(src_k, cpos); V[e] = at32(src_i, cpos); }           \
   }
   KVC_RANK_LOAD_TILE(0, key, val)
   // (explicit, so that the loop body starts with no load the compiler still has to
@@ -229,11 +245,11 @@ __device__ __forceinline__ void radix_pass(RankShared& sh, int n, const float* _
         const int32_t v = sh.stage_v[slot];
         const uint32_t dst = sh.gbase[(k >> shift) & 255u] + (uint32_t)slot;
         if (PASS == 3) {
-          dst_f[dst] = desc_key_to_float(k);
-          dst_i[dst] = v;
+          at32(dst_f, dst) = desc_key_to_float(k);
+          at32(dst_i, dst) = v;
         } else {
-          dst_k[dst] = k;
-          dst_i[dst] = v;
+          at32(dst_k, dst) = k;
+          at32(dst_i, dst) = v;
         }
       }
     }
