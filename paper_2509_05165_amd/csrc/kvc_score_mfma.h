@@ -134,15 +134,19 @@ __device__ __forceinline__ void stats_slice(int i, const f32x16& x0, const f32x1
 
 // EMIT: reduce one 32x32 logit tile (queries on rows) over its 32 query rows:
 // max of t, or sum of 2^t, with t = logit*c2 - lse2.  Result in both half-waves.
+// TASK_MAX: the accumulators were started from -lse2/c2 (nl holds that), so they
+// already are t/c2; the maximum commutes with the positive factor c2, which is
+// applied once at the end instead of once per element.
 template <bool TASK_MAX>
 __device__ __forceinline__ float emit_fold(const f32x16& acc, float c2, const float (&nl)[16]) {
   float v = TASK_MAX ? NEG_BIG : 0.f;
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
-    const float t = fmaf(acc[r], c2, nl[r]);
-    v = TASK_MAX ? fmaxf(v, t) : v + fast_exp2(t);
+    if (TASK_MAX) v = fmaxf(v, acc[r]);
+    else v += fast_exp2(fmaf(acc[r], c2, nl[r]));
   }
-  return cross_half<TASK_MAX>(v);
+  v = cross_half<TASK_MAX>(v);
+  return TASK_MAX ? v * c2 : v;
 }
 // The same for two tiles in 16 slices: slice i handles elements 2(i%8), 2(i%8)+1 of
 // tile i/8; the cross-half combine of a tile follows its last slice.
@@ -152,10 +156,16 @@ __device__ __forceinline__ void emit_slice(int i, const f32x16& x0, const f32x16
   const int b = i >> 3, r = 2 * (i & 7);
   const f32x16& x = b ? x1 : x0;
   if ((i & 7) == 0) v[b] = TASK_MAX ? NEG_BIG : 0.f;
-  const float t0 = fmaf(x[r], c2, nl[b][r]), t1 = fmaf(x[r + 1], c2, nl[b][r + 1]);
-  if (TASK_MAX) v[b] = fmaxf(v[b], fmaxf(t0, t1));
-  else v[b] += fast_exp2(t0) + fast_exp2(t1);
-  if ((i & 7) == 7) v[b] = cross_half<TASK_MAX>(v[b]);
+  if (TASK_MAX) {
+    v[b] = fmaxf(v[b], fmaxf(x[r], x[r + 1]));
+  } else {
+    const float t0 = fmaf(x[r], c2, nl[b][r]), t1 = fmaf(x[r + 1], c2, nl[b][r + 1]);
+    v[b] += fast_exp2(t0) + fast_exp2(t1);
+  }
+  if ((i & 7) == 7) {
+    v[b] = cross_half<TASK_MAX>(v[b]);
+    if (TASK_MAX) v[b] *= c2;
+  }
 }
 
 // 16 bytes per lane from (scalar base + per-lane byte offset) into LDS.
@@ -302,7 +312,10 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
   };
   auto mfma_tile = [&](f32x16 (&a)[2], const uint4 (&kf)[8]) {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) { a[0][r] = 0.f; a[1][r] = 0.f; }
+    for (int r = 0; r < 16; ++r) {
+      a[0][r] = (EMIT && TASK_MAX) ? nl[0][r] : 0.f;
+      a[1][r] = (EMIT && TASK_MAX) ? nl[1][r] : 0.f;
+    }
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
       const bf16x8 kfr = as_bf16x8(kf[ks]);
@@ -458,6 +471,13 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
         nl[qb][4 * i + 0] = v.x; nl[qb][4 * i + 1] = v.y; nl[qb][4 * i + 2] = v.z; nl[qb][4 * i + 3] = v.w;
       }
     }
+    if (TASK_MAX) {   // accumulators start from -lse2/c2 (see emit_fold)
+      const float inv_c2 = 1.f / c2;
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) nl[qb][r] *= inv_c2;
+    }
   }
 
   // tiles [0, npipe) run through the software pipeline
@@ -499,7 +519,14 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
         for (int i = 0; i < 16; ++i) {
           const int ks = i >> 1, qb = i & 1;
           const bf16x8 kfr = as_bf16x8(kf[ks]);
-          const f32x16 cin = ks == 0 ? zero : acc[p][qb];
+          f32x16 cin = acc[p][qb];
+          if (ks == 0) {
+            cin = zero;
+            if (EMIT && TASK_MAX) {
+#pragma unroll
+              for (int r = 0; r < 16; ++r) cin[r] = nl[qb][r];
+            }
+          }
           if (EMIT)   // rows = queries, columns = keys
             acc[p][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(qf[qb][ks]), kfr, cin, 0, 0, 0);
           else        // rows = keys, columns = queries
