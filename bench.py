@@ -25,7 +25,7 @@ PEAK_HBM_GBPS = 8000.0
 # HBM bytes per layer of the score kernels at the config-2 layer shape (32/8 heads, d=128,
 # N=131072, M=64), from rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by the copy-probe factors
 # (2.000 / 1.000); source: profiles/score_mfma_config2_hbm_traffic.md
-MEASURED_TRAFFIC_BYTES = {"score_mfma<stats>": 275.8e6, "score_mfma<emit>": 282.2e6}
+MEASURED_TRAFFIC_BYTES = {"score_mfma<stats>": 275.8e6, "score_mfma<emit>": 279.1e6}
 
 
 def log(msg):
