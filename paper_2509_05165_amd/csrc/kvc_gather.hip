@@ -24,6 +24,13 @@ namespace {
 constexpr int GA_THREADS = 256;
 constexpr int GA_BATCH = 2;   // row groups in flight per lane (measured: 2 beats 1, 3, 4 and 8)
 
+// Every byte the gather moves is touched once, so loads and stores carry the
+// streaming (non-temporal) hint: measured 0.70 -> 0.63 ms at the 128k shape,
+// most of it from the stores.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ u32x4 load_stream(const u32x4* p) { return __builtin_nontemporal_load(p); }
+__device__ __forceinline__ void store_stream(u32x4* p, u32x4 v) { __builtin_nontemporal_store(v, p); }
+
 // Each wave takes 64 consecutive rows of the output pool.  Lane i first resolves
 // pool row (group*64 + i): which (sequence, layer) block it lies in (binary
 // search in `offsets`), its head and rank inside the block, and from `idx` the
@@ -77,7 +84,7 @@ __global__ __launch_bounds__(GA_THREADS) void gather_kernel(
     }
     // ---- copy the 64 rows, GA_BATCH wave instructions of loads in flight ----
     for (int s0 = 0; s0 < steps; s0 += GA_BATCH) {
-      uint4 kd[GA_BATCH], vd[GA_BATCH];
+      u32x4 kd[GA_BATCH], vd[GA_BATCH];
       uint64_t kp[GA_BATCH], vp[GA_BATCH];
 #pragma unroll
       for (int j = 0; j < GA_BATCH; ++j) {
@@ -94,14 +101,14 @@ __global__ __launch_bounds__(GA_THREADS) void gather_kernel(
       }
 #pragma unroll
       for (int j = 0; j < GA_BATCH; ++j) {
-        if (kp[j]) kd[j] = reinterpret_cast<const uint4*>(kp[j])[piece];
-        if (vp[j]) vd[j] = reinterpret_cast<const uint4*>(vp[j])[piece];
+        if (kp[j]) kd[j] = load_stream(reinterpret_cast<const u32x4*>(kp[j]) + piece);
+        if (vp[j]) vd[j] = load_stream(reinterpret_cast<const u32x4*>(vp[j]) + piece);
       }
 #pragma unroll
       for (int j = 0; j < GA_BATCH; ++j) {
         const int64_t orow = group * 64 + (s0 + j) * rows_per_step + sub;
-        if (kp[j]) k_out[(size_t)orow * pieces + piece] = kd[j];
-        if (vp[j]) v_out[(size_t)orow * pieces + piece] = vd[j];
+        if (kp[j]) store_stream(reinterpret_cast<u32x4*>(k_out) + ((size_t)orow * pieces + piece), kd[j]);
+        if (vp[j]) store_stream(reinterpret_cast<u32x4*>(v_out) + ((size_t)orow * pieces + piece), vd[j]);
       }
     }
   }
@@ -181,13 +188,15 @@ __global__ __launch_bounds__(1024) void order_compact(const uint32_t* __restrict
   }
 }
 
-// Plain streaming copy (16 bytes per lane), used only to calibrate hardware
-// counters against a known byte count.
+// Plain streaming copy (16 bytes per lane, same hints as the gather), used to
+// calibrate hardware counters against a known byte count and as the copy rate
+// the gather is compared with.
 __global__ __launch_bounds__(256) void copy_probe_kernel(const uint4* __restrict__ src,
                                                          uint4* __restrict__ dst, size_t n16) {
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16;
        i += (size_t)gridDim.x * blockDim.x)
-    dst[i] = src[i];
+    store_stream(reinterpret_cast<u32x4*>(dst) + i,
+                 load_stream(reinterpret_cast<const u32x4*>(src) + i));
 }
 
 }  // namespace

@@ -39,8 +39,10 @@ __device__ __forceinline__ int acc_row(int r, int half) { return 8 * (r >> 2) + 
 // 16 bytes per lane straight from global memory into LDS: lane i of the wave
 // writes LDS bytes [lds_base + 16 i, +16).  lds_base must be wave-uniform.  The
 // load is tracked by vmcnt only; the caller orders it with wait_vmcnt + barrier.
+// K is read once per pass and a layer's K exceeds every cache, so the loads carry
+// the streaming hint (keeps the partial results of the pass in L2 instead).
 __device__ __forceinline__ void lds_dma16(const void* gptr, uint32_t lds_base) {
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr)
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off nt" ::"s"(lds_base), "v"(gptr)
                : "memory");
 }
 template <int N>
@@ -170,7 +172,7 @@ __device__ __forceinline__ void emit_slice(int i, const f32x16& x0, const f32x16
 
 // 16 bytes per lane from (scalar base + per-lane byte offset) into LDS.
 __device__ __forceinline__ void lds_dma16_s(const void* sbase, uint32_t voff, uint32_t lds_base) {
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(sbase)
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2 nt" ::"s"(lds_base), "v"(voff), "s"(sbase)
                : "memory");
 }
 
