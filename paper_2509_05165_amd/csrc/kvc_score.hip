@@ -429,7 +429,12 @@ kvc_status launch_score(const Problem& pb, const void* const* q, const void* con
     for (int l = 0; l < pb.layers; ++l) { qt.p[l] = q[l]; kt.p[l] = k[l]; }
     float* part_all = separate ? reinterpret_cast<float*>(w + L.off_part) : S;
     const size_t out_stride = separate ? L.part_layer : size_t(pb.hkv) * total;
-    dim3 grid(chunks, pb.hkv * L.row_chunks, pb.batch * pb.layers);
+    // grid.x: the (sequence, chunk) pairs of the batch, no empty slots
+    int flat_chunks = 0;
+    for (int b = 0; b < pb.batch; ++b)
+      flat_chunks += (pb.seq.cu[b + 1] - pb.seq.cu[b] + chunk - 1) / chunk;
+    if ((chunk & (chunk - 1)) != 0) { set_error("internal: chunk length %d not a power of two", chunk); return KVC_ERR_INVALID_ARG; }
+    dim3 grid(flat_chunks > 0 ? flat_chunks : 1, pb.hkv * L.row_chunks, pb.layers);
     const int nqb0 = (pb.group * pb.window < MF_RCHUNK ? pb.group * pb.window : MF_RCHUNK) / 32;
     const int rows_all = L.rows_layer * pb.layers;
 #define KVC_SCORE_MFMA(NAME, EMIT, TMAX, WQ, PM, PS, LSE, OUT)                                   \

@@ -176,7 +176,7 @@ __device__ __forceinline__ void lds_dma16_s(const void* sbase, uint32_t voff, ui
                : "memory");
 }
 
-// grid: (chunks, Hkv * row_chunks, Lyr * Bt), 256 threads.  WQ = waves along the query
+// grid: ((sequence, chunk) pairs, Hkv * row_chunks, Lyr), 256 threads.  WQ = waves along the query
 // rows (each owns 2 blocks of 32 rows); the other 4/WQ waves split the key tiles.
 //
 // Schedule of one workgroup over its macro tiles (two K buffers, tile t in
@@ -207,15 +207,28 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
   __shared__ float stat[EMIT ? 1 : 4][2][32][2];               // STATS: per wave (max, sum)
   __shared__ __attribute__((aligned(16))) float lse_s[EMIT ? MF_RCHUNK : 4];   // EMIT: -lse2 of the row chunk
 
-  // blockIdx.z = layer * batch + sequence: one launch covers every layer, so that
-  // workgroups of the next layer start as those of this one finish and only the
-  // very first ones wait for their first tile with nothing else running
-  const int layer = blockIdx.z / batch, b = blockIdx.z - layer * batch;
+  // blockIdx.z = layer: one launch covers every layer, so that workgroups of the
+  // next layer start as those of this one finish and only the very first ones wait
+  // for their first tile with nothing else running.
+  // blockIdx.x runs over the (sequence, chunk) pairs of the batch, sequence by
+  // sequence: the grid holds no empty slots, and consecutive workgroup ids, which
+  // the hardware deals round-robin to the eight XCDs, carry equal work whatever the
+  // mix of sequence lengths (a chunk-major grid gave XCD j the j-th chunk of every
+  // sequence: twice the time on a batch of 5k..29k-token sequences).
+  const int layer = blockIdx.z;
+  const int chunk_shift = __builtin_ctz(chunk_keys);   // chunk_keys is a power of two (host-checked)
+  int b = 0, chunk = blockIdx.x;
+  for (; b < batch - 1; ++b) {
+    const int nc = (seq.cu[b + 1] - seq.cu[b] + chunk_keys - 1) >> chunk_shift;
+    if (chunk < nc) break;
+    chunk -= nc;
+  }
+  const int zid = layer * batch + b;
   const uint16_t* __restrict__ q_layer = static_cast<const uint16_t*>(q_tab.p[layer]);
   const uint16_t* __restrict__ k_layer = static_cast<const uint16_t*>(k_tab.p[layer]);
   if (EMIT) out += (size_t)layer * out_layer_stride;
   const int tok0 = seq.cu[b], n = seq.cu[b + 1] - tok0;
-  const int key_begin = blockIdx.x * chunk_keys;
+  const int key_begin = chunk * chunk_keys;
   if (key_begin >= n) return;
   const int key_end = min(n, key_begin + chunk_keys);
   const int hkv = gridDim.y / row_chunks;
@@ -284,7 +297,7 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
   // EMIT: minus lse2 of this row chunk goes through LDS (one coalesced load)
   float my_nl = 0.f;
   if (EMIT && (int)threadIdx.x < nqb * 32)
-    my_nl = -lse2[((size_t)blockIdx.z * hq + h * group) * window + row0 + threadIdx.x];
+    my_nl = -lse2[((size_t)zid * hq + h * group) * window + row0 + threadIdx.x];
   float nl[2][16];   // EMIT: minus lse2 of the lane's accumulator rows, filled after the first barrier
 
   float mrun[2] = {NEG_BIG, NEG_BIG}, srun[2] = {0.f, 0.f};   // STATS, in log2 units
@@ -613,11 +626,11 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
         ss += stat[k2 * WQ + sq][qb][j][1] * fast_exp2(stat[k2 * WQ + sq][qb][j][0] - mm);
       const int r = row0 + blk * 32 + j;
       // row index over all layers and sequences of the launch
-      const size_t qrow = ((size_t)blockIdx.z * hq + h * group) * window + r;
+      const size_t qrow = ((size_t)zid * hq + h * group) * window + r;
       // partial statistics are stored chunk-major so the merge reads coalesced
-      const size_t rows_all = (size_t)gridDim.z * hq * window;
-      part_m[(size_t)blockIdx.x * rows_all + qrow] = mm;
-      part_s[(size_t)blockIdx.x * rows_all + qrow] = ss;
+      const size_t rows_all = (size_t)gridDim.z * batch * hq * window;
+      part_m[(size_t)chunk * rows_all + qrow] = mm;
+      part_s[(size_t)chunk * rows_all + qrow] = ss;
     }
   }
 }
