@@ -22,6 +22,7 @@ import numpy as np  # noqa: E402
 METRIC = "context tokens compressed/sec at Llama-3-8B shape, L=128k"
 PEAK_BF16_MFMA_TFLOPS = 2500.0
 PEAK_HBM_GBPS = 8000.0
+PEAK_FP32_VALU_TFLOPS = 157.3   # 256 CUs x 4 SIMDs x 64 lanes x 2 flops x 2.4 GHz, doubled by packed issue
 # HBM bytes per layer of the score kernels at the config-2 layer shape (32/8 heads, d=128,
 # N=131072, M=64), from rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by the copy-probe factors
 # (2.000 / 1.000); source: profiles/score_mfma_config2_hbm_traffic.md
@@ -201,6 +202,25 @@ def main():
                                 if layer_shape and dom in MEASURED_TRAFFIC_BYTES else None),
                     "avg_launch_us": avg_s * 1e6, "launches_per_step": c,
                     "layers_per_launch": layers_per_launch}
+    elif dom == "gather_kernel":
+        # per retained composite token and KV head: K and V rows read and written + one index
+        c, ms = per_step[dom]
+        esz_ = 2 if cfg.dtype == "bf16" else 4
+        bytes_per_launch = tb * cfg.hkv * (4.0 * cfg.head_dim * esz_ + 4) / c
+        avg_s = ms / c * 1e-3
+        achieved = bytes_per_launch / avg_s / 1e9
+        roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": PEAK_HBM_GBPS,
+                    "unit": "GB/s", "frac": achieved / PEAK_HBM_GBPS, "traffic": None,
+                    "avg_launch_us": avg_s * 1e6, "launches_per_step": c}
+    elif dom.startswith("score_"):
+        # generic fp32 kernels (vector ALU, no matrix cores): 2*d flops per logit
+        c, ms = per_step[dom]
+        flops_per_launch = 2.0 * cfg.hq * cfg.window * cfg.head_dim * total * cfg.layers / c
+        avg_s = ms / c * 1e-3
+        achieved = flops_per_launch / avg_s / 1e12
+        roofline = {"bound": "alu", "kernel": dom, "achieved": achieved, "peak": PEAK_FP32_VALU_TFLOPS,
+                    "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_VALU_TFLOPS, "traffic": None,
+                    "avg_launch_us": avg_s * 1e6, "launches_per_step": c}
     stages = {
         "score_ms": sum(ms for k, (c, ms) in per_step.items() if k.startswith("score")),
         "rank_ms": sum(ms for k, (c, ms) in per_step.items() if k.startswith("head_rank")),
