@@ -103,7 +103,7 @@ struct RankShared {
 // element base + w*64*ITEMS + e*64 + l, which is also its order inside the tile.
 // LIN / LOUT (single-tile segments only): the pass reads its (key, value) pairs
 // from / leaves them in the LDS staging area, in slot order.
-template <int PASS, bool LIN, bool LOUT>
+template <int PASS, bool LIN, bool LOUT, int ITEMS>
 __device__ __forceinline__ void radix_pass(RankShared& sh, int n, const float* __restrict__ src_f,
                                            const uint32_t* __restrict__ src_k,
                                            const int32_t* __restrict__ src_i,
@@ -111,6 +111,7 @@ __device__ __forceinline__ void radix_pass(RankShared& sh, int n, const float* _
                                            int32_t* __restrict__ dst_i,
                                            float* __restrict__ dst_f) {
   constexpr int shift = PASS * 8;
+  constexpr int TILE = RK_THREADS * ITEMS;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   src_f = uniform_ptr(src_f); src_k = uniform_ptr(src_k); src_i = uniform_ptr(src_i);
   dst_k = uniform_ptr(dst_k); dst_i = uniform_ptr(dst_i); dst_f = uniform_ptr(dst_f);
@@ -134,12 +135,12 @@ __device__ __forceinline__ void radix_pass(RankShared& sh, int n, const float* _
   }
   __syncthreads();
 
-  uint32_t key[RK_ITEMS], nkey[RK_ITEMS];
-  int32_t val[RK_ITEMS], nval[RK_ITEMS];
-  const int woff = wave * 64 * RK_ITEMS + lane;
+  uint32_t key[ITEMS], nkey[ITEMS];
+  int32_t val[ITEMS], nval[ITEMS];
+  const int woff = wave * 64 * ITEMS + lane;
   // loads of one tile; positions past the segment re-read its last element
 #define KVC_RANK_LOAD_TILE(BASE, K, V)                         \
-  _Pragma("unroll") for (int e = 0; e < RK_ITEMS; ++e) {       \
+  _Pragma("unroll") for (int e = 0; e < ITEMS; ++e) {       \
     const int pos = (BASE) + woff + e * 64;                    \
     const uint32_t cpos = uint32_t(pos < n ? pos : n - 1);     /* unsigned: 32-bit offset addressing */ \
     if (PASS == 0) { K[e] = __float_as_uint(at32(src_f, cpos)); V[e] = int32_t(cpos); } \
@@ -151,16 +152,16 @@ __device__ __forceinline__ void radix_pass(RankShared& sh, int n, const float* _
   // wait for: see the wait before the scatter)
   if (!LIN) __builtin_amdgcn_s_waitcnt(0x0F70);
 
-  for (int base = 0; base < n; base += RK_TILE) {
+  for (int base = 0; base < n; base += TILE) {
     // next tile's loads fly while this one is ranked and scattered
-    const int nbase = base + RK_TILE < n ? base + RK_TILE : base;
+    const int nbase = base + TILE < n ? base + TILE : base;
     if (!LIN && !LOUT) { KVC_RANK_LOAD_TILE(nbase, nkey, nval) }   // a single tile has no next one
     if (PASS == 0) {
 #pragma unroll
-      for (int e = 0; e < RK_ITEMS; ++e) key[e] = desc_key(__uint_as_float(key[e]));
+      for (int e = 0; e < ITEMS; ++e) key[e] = desc_key(__uint_as_float(key[e]));
     }
 
-    uint32_t rank[RK_ITEMS];
+    uint32_t rank[ITEMS];
     const int wbase = base + woff;
     // zero this wave's counters (only this wave touches them until the barrier)
 #pragma unroll
@@ -168,7 +169,7 @@ __device__ __forceinline__ void radix_pass(RankShared& sh, int n, const float* _
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
-    for (int e = 0; e < RK_ITEMS; ++e) {
+    for (int e = 0; e < ITEMS; ++e) {
       const bool valid = wbase + e * 64 < n;
       const uint64_t vmask = __ballot(valid);
       const uint32_t digit = (key[e] >> shift) & 255u;
@@ -215,7 +216,7 @@ __device__ __forceinline__ void radix_pass(RankShared& sh, int n, const float* _
     lds_barrier();
     // every item goes to its tile-local slot
 #pragma unroll
-    for (int e = 0; e < RK_ITEMS; ++e) {
+    for (int e = 0; e < ITEMS; ++e) {
       if (wbase + e * 64 < n) {
         const uint32_t digit = (key[e] >> shift) & 255u;
         const uint32_t slot = sh.tstart[digit] + sh.wave_cnt[wave][digit] + rank[e];
@@ -231,14 +232,14 @@ __device__ __forceinline__ void radix_pass(RankShared& sh, int n, const float* _
     if (!LIN && !LOUT) {
       __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
 #pragma unroll
-      for (int e = 0; e < RK_ITEMS; ++e) { key[e] = nkey[e]; val[e] = nval[e]; }
+      for (int e = 0; e < ITEMS; ++e) { key[e] = nkey[e]; val[e] = nval[e]; }
     }
     // consecutive threads write consecutive global slots within a digit run
     // (single tile with LOUT: slot order is the order of this pass; it stays in LDS)
-    const int tile_n = min(RK_TILE, n - base);
+    const int tile_n = min(TILE, n - base);
     if (!LOUT) {
 #pragma unroll
-    for (int e = 0; e < RK_ITEMS; ++e) {
+    for (int e = 0; e < ITEMS; ++e) {
       const int slot = e * RK_THREADS + tid;
       if (slot < tile_n) {
         const uint32_t k = sh.stage_k[slot];
@@ -292,17 +293,23 @@ __global__ __launch_bounds__(RK_THREADS) void head_rank_kernel(
   }
   __syncthreads();
 
-  if (n <= RK_TILE) {   // one tile: the passes hand the data on through LDS
-    radix_pass<0, false, true>(sh, n, src_f, nullptr, nullptr, nullptr, nullptr, nullptr);
-    radix_pass<1, true, true>(sh, n, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr);
-    radix_pass<2, true, true>(sh, n, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr);
-    radix_pass<3, true, false>(sh, n, nullptr, nullptr, nullptr, nullptr, b_idx, sorted_out + seg);
-    return;
-  }
-  radix_pass<0, false, false>(sh, n, src_f, nullptr, nullptr, a_keys, a_idx, nullptr);
-  radix_pass<1, false, false>(sh, n, nullptr, a_keys, a_idx, b_keys, b_idx, nullptr);
-  radix_pass<2, false, false>(sh, n, nullptr, b_keys, b_idx, a_keys, a_idx, nullptr);
-  radix_pass<3, false, false>(sh, n, nullptr, a_keys, a_idx, nullptr, b_idx, sorted_out + seg);
+  // one tile: the passes hand the data on through LDS; short segments take fewer
+  // items per lane (an unused item slot costs as much ranking work as a used one)
+#define KVC_RANK_ONE_TILE(ITEMS)                                                                        \
+  do {                                                                                                  \
+    radix_pass<0, false, true, ITEMS>(sh, n, src_f, nullptr, nullptr, nullptr, nullptr, nullptr);       \
+    radix_pass<1, true, true, ITEMS>(sh, n, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr);      \
+    radix_pass<2, true, true, ITEMS>(sh, n, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr);      \
+    radix_pass<3, true, false, ITEMS>(sh, n, nullptr, nullptr, nullptr, nullptr, b_idx, sorted_out + seg); \
+  } while (0)
+  if (n <= RK_THREADS * 2) { KVC_RANK_ONE_TILE(2); return; }
+  if (n <= RK_THREADS * 4) { KVC_RANK_ONE_TILE(4); return; }
+  if (n <= RK_TILE) { KVC_RANK_ONE_TILE(RK_ITEMS); return; }
+#undef KVC_RANK_ONE_TILE
+  radix_pass<0, false, false, RK_ITEMS>(sh, n, src_f, nullptr, nullptr, a_keys, a_idx, nullptr);
+  radix_pass<1, false, false, RK_ITEMS>(sh, n, nullptr, a_keys, a_idx, b_keys, b_idx, nullptr);
+  radix_pass<2, false, false, RK_ITEMS>(sh, n, nullptr, b_keys, b_idx, a_keys, a_idx, nullptr);
+  radix_pass<3, false, false, RK_ITEMS>(sh, n, nullptr, a_keys, a_idx, nullptr, b_idx, sorted_out + seg);
 }
 
 // grid: (token blocks, layers)

@@ -219,6 +219,30 @@ __global__ __launch_bounds__(256) void score_merge(SeqTable seq, int rows_per_se
   }
 }
 
+// Same merge, one thread per row: for sequences of a few chunks (the 4096-token
+// regime has one), where sixteen lanes per row would mostly idle.
+__global__ __launch_bounds__(256) void score_merge_few(SeqTable seq, int rows_per_seq, int layers,
+                                                       int chunk_keys,
+                                                       const float* __restrict__ part_m,
+                                                       const float* __restrict__ part_s,
+                                                       float* __restrict__ lse2) {
+  const int rows = rows_per_seq * seq.batch * layers;
+  const int row = blockIdx.x * 256 + threadIdx.x;
+  if (row >= rows) return;
+  const int b = (row / rows_per_seq) % seq.batch;
+  const int n = seq.cu[b + 1] - seq.cu[b];
+  const int chunks = (n + chunk_keys - 1) / chunk_keys;
+  if (chunks == 0) return;
+  float mm = NEG_BIG, acc = 0.f;
+  for (int c = 0; c < chunks; ++c) {
+    const float m2 = part_m[(size_t)c * rows + row], s2 = part_s[(size_t)c * rows + row];
+    const float mn = fmaxf(mm, m2);
+    acc = acc * fast_exp2(mm - mn) + s2 * fast_exp2(m2 - mn);
+    mm = mn;
+  }
+  lse2[row] = mm + __log2f(acc);
+}
+
 // ---------------------------------------------------------------------------
 // finish: combine row-chunk partials, normalise the group mean, add head mean.
 // One thread per token; in place when part == S and row_chunks == 1.  blockIdx.y
@@ -449,8 +473,13 @@ kvc_status launch_score(const Problem& pb, const void* const* q, const void* con
   } while (0)
     if (chunks > 0) {
       KVC_SCORE_MFMA_WQ("score_mfma<stats>", false, true, part_m, part_s, nullptr, nullptr);
-      KVC_LAUNCH("score_merge", stream, score_merge<<<(rows_all + MERGE_ROWS - 1) / MERGE_ROWS, 256, 0, stream>>>(
-          pb.seq, rows_per_seq, pb.layers, chunk, part_m, part_s, lse2));
+      if (chunks <= 4) {
+        KVC_LAUNCH("score_merge", stream, score_merge_few<<<(rows_all + 255) / 256, 256, 0, stream>>>(
+            pb.seq, rows_per_seq, pb.layers, chunk, part_m, part_s, lse2));
+      } else {
+        KVC_LAUNCH("score_merge", stream, score_merge<<<(rows_all + MERGE_ROWS - 1) / MERGE_ROWS, 256, 0, stream>>>(
+            pb.seq, rows_per_seq, pb.layers, chunk, part_m, part_s, lse2));
+      }
       if (task_max) {
         KVC_SCORE_MFMA_WQ("score_mfma<emit>", true, true, nullptr, nullptr, lse2, part_all);
       } else {
