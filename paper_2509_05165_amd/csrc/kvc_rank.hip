@@ -282,14 +282,43 @@ __global__ __launch_bounds__(RK_THREADS) void head_rank_kernel(
   const int tid = threadIdx.x;
 
   // ---- histograms of all four digits in one sweep ----
-  for (int i = tid; i < 4 * RK_BINS; i += RK_THREADS) (&sh.hist[0][0])[i] = 0;
+  // Eight loads in flight per thread.  The top digit (sign and high exponent bits)
+  // takes three or four values in a whole segment, so its atomics would all hit one
+  // address; it is counted in 32 bank-private copies instead, which live in the
+  // staging area (unused until the first pass) and are summed afterwards.
+  static_assert(RK_TILE >= RK_BINS * 32, "staging area holds the 32 copies");
+  uint32_t* top_copies = sh.stage_k;
+  for (int i = tid; i < 3 * RK_BINS; i += RK_THREADS) (&sh.hist[0][0])[i] = 0;
+  for (int i = tid; i < RK_BINS * 32; i += RK_THREADS) top_copies[i] = 0;
   __syncthreads();
-  for (int i = tid; i < n; i += RK_THREADS) {
-    const uint32_t key = desc_key(src_f[i]);
-    atomicAdd(&sh.hist[0][key & 255u], 1u);
-    atomicAdd(&sh.hist[1][(key >> 8) & 255u], 1u);
-    atomicAdd(&sh.hist[2][(key >> 16) & 255u], 1u);
-    atomicAdd(&sh.hist[3][key >> 24], 1u);
+  {
+    const float* sweep_f = uniform_ptr(src_f);
+    const int bank = tid & 31;
+    for (int i0 = 0; i0 < n; i0 += RK_THREADS * 8) {
+      float x[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int i = i0 + e * RK_THREADS + tid;
+        x[e] = at32(sweep_f, uint32_t(i < n ? i : n - 1));   // clamped: never past the segment
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        if (i0 + e * RK_THREADS + tid < n) {
+          const uint32_t key = desc_key(x[e]);
+          atomicAdd(&sh.hist[0][key & 255u], 1u);
+          atomicAdd(&sh.hist[1][(key >> 8) & 255u], 1u);
+          atomicAdd(&sh.hist[2][(key >> 16) & 255u], 1u);
+          atomicAdd(&top_copies[(key >> 24) * 32 + bank], 1u);
+        }
+      }
+    }
+  }
+  __syncthreads();
+  if (tid < RK_BINS) {
+    uint32_t sum = 0;
+#pragma unroll 8
+    for (int j = 0; j < 32; ++j) sum += top_copies[tid * 32 + ((j + tid) & 31)];
+    sh.hist[3][tid] = sum;
   }
   __syncthreads();
 
