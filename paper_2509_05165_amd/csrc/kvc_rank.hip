@@ -356,6 +356,32 @@ __global__ void composite_kernel(const float* __restrict__ sorted, int hkv, int 
   I[(size_t)l * total + c] = head_max ? acc : acc / float(hkv);
 }
 
+// The same for HKV heads known at compile time: the loads of a thread are
+// independent and in flight together; VEC consecutive ranks per thread.
+template <int HKV, int VEC>
+__global__ __launch_bounds__(256) void composite_plain(const float* __restrict__ sorted, int total,
+                                                       int head_max, float* __restrict__ I) {
+  typedef float vec_t __attribute__((ext_vector_type(VEC)));
+  const int c = (blockIdx.x * 256 + threadIdx.x) * VEC;
+  if (c >= total) return;                       // total is a multiple of VEC (host-checked)
+  const int l = blockIdx.y;
+  const float* p = sorted + (size_t)l * HKV * total + c;
+  vec_t x[HKV];
+#pragma unroll
+  for (int h = 0; h < HKV; ++h) x[h] = __builtin_nontemporal_load(reinterpret_cast<const vec_t*>(p + (size_t)h * total));
+  vec_t acc = x[0];
+#pragma unroll
+  for (int h = 1; h < HKV; ++h) {               // fixed head order, as in the general kernel
+    if (head_max) {
+#pragma unroll
+      for (int j = 0; j < VEC; ++j) acc[j] = fmaxf(acc[j], x[h][j]);
+    } else {
+      acc += x[h];
+    }
+  }
+  *reinterpret_cast<vec_t*>(I + (size_t)l * total + c) = head_max ? acc : acc / float(HKV);
+}
+
 }  // namespace
 
 size_t rank_workspace_bytes(const Problem& pb) {
@@ -376,9 +402,20 @@ kvc_status launch_head_rank(const Problem& pb, const float* S, int32_t* idx, flo
 
 kvc_status launch_composite(const Problem& pb, const float* S_sorted, float* I,
                             hipStream_t stream) {
-  dim3 grid((unsigned)((pb.total + 255) / 256), pb.layers);
-  KVC_LAUNCH("composite_kernel", stream, composite_kernel<<<grid, 256, 0, stream>>>(S_sorted, pb.hkv, int(pb.total),
-                                             pb.agg_head == KVC_AGG_MAX, I));
+  const int total = int(pb.total), head_max = pb.agg_head == KVC_AGG_MAX;
+  // four ranks per thread need 16-byte aligned rows in every layer
+  const bool vec4 = total % 4 == 0 &&
+                    (reinterpret_cast<uintptr_t>(S_sorted) | reinterpret_cast<uintptr_t>(I)) % 16 == 0;
+  if (pb.hkv == 8 && vec4) {
+    dim3 grid((unsigned)((total / 4 + 255) / 256), pb.layers);
+    KVC_LAUNCH("composite_kernel", stream, composite_plain<8, 4><<<grid, 256, 0, stream>>>(S_sorted, total, head_max, I));
+  } else if (pb.hkv == 8) {
+    dim3 grid((unsigned)((total + 255) / 256), pb.layers);
+    KVC_LAUNCH("composite_kernel", stream, composite_plain<8, 1><<<grid, 256, 0, stream>>>(S_sorted, total, head_max, I));
+  } else {
+    dim3 grid((unsigned)((total + 255) / 256), pb.layers);
+    KVC_LAUNCH("composite_kernel", stream, composite_kernel<<<grid, 256, 0, stream>>>(S_sorted, pb.hkv, total, head_max, I));
+  }
   return KVC_OK;
 }
 

@@ -333,6 +333,32 @@ __global__ void score_finish(const float* part, FinishArgs a, SeqTable seq, floa
     S[(size_t)h * total + c] = finish_group_value(part, a, h, c, vnorm) + mean;
 }
 
+// The common case of the finish (one row chunk per KV head, no value norms, no
+// forced retention, HKV heads known at compile time): all loads of a thread are
+// independent and in flight together; VEC consecutive tokens per thread.
+template <int HKV, int VEC>
+__global__ __launch_bounds__(256) void score_finish_plain(const float* part, float* S, int total,
+                                                          float group_norm, int add_head_mean,
+                                                          size_t part_layer_stride,
+                                                          size_t layer_stride) {
+  typedef float vec_t __attribute__((ext_vector_type(VEC)));
+  const int c = (blockIdx.x * 256 + threadIdx.x) * VEC;
+  if (c >= total) return;                       // total is a multiple of VEC (host-checked)
+  part += blockIdx.y * part_layer_stride;
+  S += blockIdx.y * layer_stride;
+  vec_t v[HKV];
+#pragma unroll
+  for (int h = 0; h < HKV; ++h)
+    v[h] = *reinterpret_cast<const vec_t*>(part + (size_t)h * total + c) * group_norm;
+  vec_t sum = v[0];
+#pragma unroll
+  for (int h = 1; h < HKV; ++h) sum += v[h];    // same order as the general kernel
+  const vec_t mean = add_head_mean ? sum / float(HKV) : (vec_t)(0.f);
+#pragma unroll
+  for (int h = 0; h < HKV; ++h)
+    *reinterpret_cast<vec_t*>(S + (size_t)h * total + c) = v[h] + mean;
+}
+
 // ---------------------------------------------------------------------------
 // value norms of one layer: w[h, c] = ||V[h, c, :]||_2 in fp32.  A group of
 // 16 lanes squares and sums one row (16 bytes per lane and step), four rows
@@ -498,8 +524,24 @@ kvc_status launch_score(const Problem& pb, const void* const* q, const void* con
             part_all + size_t(l) * out_stride, fa, pb.seq, S + size_t(l) * pb.hkv * total, 0, 0, vnorm));
       }
     } else if (pb.layers > 0 && total > 0) {
-      KVC_LAUNCH("score_finish", stream, score_finish<<<dim3((total + 255) / 256, pb.layers), 256, 0, stream>>>(
-          part_all, fa, pb.seq, S, out_stride, size_t(pb.hkv) * total, nullptr));
+      const bool plain = L.row_chunks == 1 && pb.keep_first == 0 && pb.keep_last == 0 &&
+                         (pb.hkv == 8 || pb.hkv == 4);
+      // four tokens per thread need 16-byte aligned rows in every layer
+      const bool vec4 = total % 4 == 0 && out_stride % 4 == 0 &&
+                        (reinterpret_cast<uintptr_t>(part_all) | reinterpret_cast<uintptr_t>(S)) % 16 == 0;
+      const size_t s_stride = size_t(pb.hkv) * total;
+#define KVC_FINISH_PLAIN(HKV, VEC)                                                              \
+  KVC_LAUNCH("score_finish", stream,                                                            \
+             score_finish_plain<HKV, VEC><<<dim3((total / VEC + 255) / 256, pb.layers), 256, 0, stream>>>( \
+                 part_all, S, total, fa.group_norm, pb.add_head_mean, out_stride, s_stride))
+      if (plain && pb.hkv == 8 && vec4) KVC_FINISH_PLAIN(8, 4);
+      else if (plain && pb.hkv == 8) KVC_FINISH_PLAIN(8, 1);
+      else if (plain && pb.hkv == 4 && vec4) KVC_FINISH_PLAIN(4, 4);
+      else if (plain && pb.hkv == 4) KVC_FINISH_PLAIN(4, 1);
+      else
+        KVC_LAUNCH("score_finish", stream, score_finish<<<dim3((total + 255) / 256, pb.layers), 256, 0, stream>>>(
+            part_all, fa, pb.seq, S, out_stride, s_stride, nullptr));
+#undef KVC_FINISH_PLAIN
     }
     return KVC_OK;
   }
