@@ -10,6 +10,11 @@
 // layer order until the budget is met (within a layer the tied entries are the
 // ranks right after the ones above the threshold, so each layer keeps a prefix).
 //
+// The digit search after a histogram pass and the final bookkeeping run in the
+// last workgroup of the sequence to finish (each workgroup takes a ticket once its
+// atomic updates are complete; the one that draws the last ticket reads the totals
+// with device-scope atomic loads), so a call is five launches instead of eleven.
+//
 // A "layer" here is a row of the pool: a layer, or a (layer, head) pair in the
 // unstructured variant.  With a per-row floor f the first f ranks of every row
 // are kept unconditionally and stay out of the histograms; the budget that is
@@ -47,62 +52,101 @@ __global__ void select_init(uint32_t* hist, int count, SelState* state, BudgetTa
   if (i < batch) { state[i].prefix = 0; state[i].pad = 0; state[i].remaining = (uint64_t)budget.b[i]; }
 }
 
-// grid: (token blocks, layers, batch)
-__global__ __launch_bounds__(SEL_THREADS) void select_hist(
-    const float* __restrict__ I, SeqTable seq, int total, int pass, int floor_rank,
-    const SelState* __restrict__ state, uint32_t* __restrict__ hist /* [batch][3][SEL_BINS] */) {
-  __shared__ uint32_t lh[SEL_BINS];
-  const int b = blockIdx.z;
-  const int tok0 = seq.cu[b], n = seq.cu[b + 1] - tok0;
-  const int begin = max(blockIdx.x * SEL_PER_BLOCK, floor_rank);   // ranks below the floor do not compete
-  if (begin >= n || begin >= (int)(blockIdx.x + 1) * SEL_PER_BLOCK) return;
-  const int end = min(n, (int)(blockIdx.x + 1) * SEL_PER_BLOCK);
-  for (int i = threadIdx.x; i < SEL_BINS; i += SEL_THREADS) lh[i] = 0;
-  __syncthreads();
-  const uint32_t want_hi = pass == 0 ? 0u : (pass == 1 ? state[b].prefix >> 21 : state[b].prefix >> 10);
-  const float* row = I + (size_t)blockIdx.y * total + tok0;
-  for (int i = begin + threadIdx.x; i < end; i += SEL_THREADS) {
-    uint32_t digit, hi;
-    digit_of(pass, float_to_ordered(row[i]), &digit, &hi);
-    if (hi == want_hi) atomicAdd(&lh[digit], 1u);
-  }
-  __syncthreads();
-  uint32_t* gh = hist + ((size_t)b * 3 + pass) * SEL_BINS;
-  for (int i = threadIdx.x; i < SEL_BINS; i += SEL_THREADS)
-    if (lh[i]) atomicAdd(&gh[i], lh[i]);
+__device__ __forceinline__ uint32_t load_agent(const uint32_t* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// grid: (batch); picks the digit whose bucket holds the wanted rank, walking
-// from the largest digit down.
-__global__ __launch_bounds__(SEL_THREADS) void select_find(int pass, const uint32_t* __restrict__ hist,
-                                                           SelState* state) {
-  __shared__ uint32_t sums[SEL_THREADS];
-  const int b = blockIdx.x;
-  const uint64_t want = state[b].remaining;
+// Ticket of a workgroup that has finished its part for sequence b: true for the
+// one that drew the last of `expected` tickets.  Workgroups hand data to the last
+// one through device-scope atomics only (histogram and count updates), which are
+// performed at the device's coherence point and are complete once the issuing
+// wave's memory counter has drained; so the release side is that wait, not a
+// device-scope fence (whose write-back of the whole L2 cost 150 us per launch
+// here, 2048 workgroups each paying it).  The last workgroup reads the totals
+// with device-scope atomic loads.
+// Tickets are drawn in two levels (groups of SEL_GROUP workgroups, then the groups
+// of a sequence), each counter on a cache line of its own: two thousand
+// workgroups drawing from one address took 30 us per launch.
+constexpr int SEL_GROUP = 64;
+constexpr int SEL_TICKET_WORDS = 32;   // one 128-byte line per counter
+
+// tickets: [4 kernels][batch][groups + 1][SEL_TICKET_WORDS]; slot `groups` is the second level
+__device__ __forceinline__ bool last_workgroup(uint32_t* tickets, int kernel_id, int batch, int b) {
+  __shared__ uint32_t is_last;
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0): my atomics have been performed
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const uint32_t nblocks = gridDim.x * gridDim.y;
+    const uint32_t groups = (nblocks + SEL_GROUP - 1) / SEL_GROUP;
+    const uint32_t flat = blockIdx.y * gridDim.x + blockIdx.x, g = flat / SEL_GROUP;
+    const uint32_t in_group = min((uint32_t)SEL_GROUP, nblocks - g * SEL_GROUP);
+    uint32_t* base = tickets + ((size_t)(kernel_id * batch + b) * (groups + 1)) * SEL_TICKET_WORDS;
+    uint32_t last = atomicAdd(base + (size_t)g * SEL_TICKET_WORDS, 1u) == in_group - 1;
+    if (last) last = atomicAdd(base + (size_t)groups * SEL_TICKET_WORDS, 1u) == groups - 1;
+    is_last = last;
+  }
+  __syncthreads();
+  const bool last = is_last != 0;
+  if (last) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+  return last;
+}
+
+// Inclusive prefix sum over the SEL_THREADS threads of a workgroup; *total = sum of all.
+__device__ __forceinline__ uint64_t block_scan_incl(uint64_t v, uint64_t* total) {
+  __shared__ uint64_t wave_tot[SEL_THREADS / 64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  uint64_t incl = v;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const uint64_t o = __shfl_up(incl, off);
+    if (lane >= off) incl += o;
+  }
+  __syncthreads();                              // the previous call's readers are done
+  if (lane == 63) wave_tot[wave] = incl;
+  __syncthreads();
+  uint64_t add = 0, tot = 0;
+#pragma unroll
+  for (int w = 0; w < SEL_THREADS / 64; ++w) {
+    const uint64_t x = wave_tot[w];
+    if (w < wave) add += x;
+    tot += x;
+  }
+  *total = tot;
+  return incl + add;
+}
+
+// One workgroup: picks the digit whose bucket holds the wanted rank, walking from
+// the largest digit down.  Thread t owns bins [bins - (t+1)*per, bins - t*per) in
+// descending order; a prefix sum over the threads names the owner of the rank.
+__device__ __forceinline__ void find_digit(int pass, int b, const uint32_t* __restrict__ hist,
+                                           SelState* state) {
+  const uint64_t want = state[b].remaining;    // uniform
   if (want == 0) return;                       // budget 0: nothing to find
   const uint32_t* gh = hist + ((size_t)b * 3 + pass) * SEL_BINS;
   const int bins = pass == 2 ? 1024 : SEL_BINS;
   const int per = bins / SEL_THREADS;          // 8 or 4 bins per thread
-  // thread t owns bins [bins - (t+1)*per, bins - t*per): descending order
   const int t = threadIdx.x;
-  uint32_t mine = 0;
-  for (int j = 0; j < per; ++j) mine += gh[bins - 1 - (t * per + j)];
-  sums[t] = mine;
-  __syncthreads();
-  if (t == 0) {
-    uint64_t run = 0;
-    int owner = SEL_THREADS - 1;
-    for (int i = 0; i < SEL_THREADS; ++i) {
-      if (run + sums[i] >= want) { owner = i; break; }
-      run += sums[i];
-    }
+  uint32_t c[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) c[j] = j < per ? load_agent(&gh[bins - 1 - (t * per + j)]) : 0u;
+  uint64_t mine = 0;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) mine += c[j];
+  uint64_t total;
+  const uint64_t incl = block_scan_incl(mine, &total);
+  uint64_t run = incl - mine;
+  // the thread whose range holds the rank; a rank past the pool ends in the last bin
+  if (run < want && (want <= incl || t == SEL_THREADS - 1)) {
     uint32_t digit = 0;
-    for (int j = 0; j < per; ++j) {
-      const int bin = bins - 1 - (owner * per + j);
-      const uint32_t c = gh[bin];
-      if (run + c >= want) { digit = (uint32_t)bin; break; }
-      run += c;
-      digit = (uint32_t)bin;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      if (j < per) {
+        const int bin = bins - 1 - (t * per + j);
+        digit = (uint32_t)bin;
+        if (run + c[j] >= want) break;
+        run += c[j];
+      }
     }
     const uint32_t shift = pass == 0 ? 21u : (pass == 1 ? 10u : 0u);
     state[b].prefix |= digit << shift;
@@ -110,41 +154,48 @@ __global__ __launch_bounds__(SEL_THREADS) void select_find(int pass, const uint3
   }
 }
 
-// grid: (token blocks, layers, batch): counts[b][l] = {#(I > tau), #(I == tau)}
-__global__ __launch_bounds__(SEL_THREADS) void select_count(
-    const float* __restrict__ I, SeqTable seq, int total, int layers, int floor_rank,
-    const SelState* __restrict__ state, uint32_t* __restrict__ counts) {
-  __shared__ uint32_t sh[2];
+// grid: (token blocks, layers, batch)
+__global__ __launch_bounds__(SEL_THREADS) void select_hist(
+    const float* __restrict__ I, SeqTable seq, int total, int pass, int floor_rank,
+    SelState* state, uint32_t* __restrict__ hist /* [batch][3][SEL_BINS] */,
+    uint32_t* __restrict__ tickets) {
+  __shared__ uint32_t lh[SEL_BINS];
   const int b = blockIdx.z;
   const int tok0 = seq.cu[b], n = seq.cu[b + 1] - tok0;
-  const int begin = max(blockIdx.x * SEL_PER_BLOCK, floor_rank);
-  if (begin >= n || begin >= (int)(blockIdx.x + 1) * SEL_PER_BLOCK) return;
-  const int end = min(n, (int)(blockIdx.x + 1) * SEL_PER_BLOCK);
-  if (threadIdx.x < 2) sh[threadIdx.x] = 0;
-  __syncthreads();
-  const uint32_t tau = state[b].prefix;
-  const float* row = I + (size_t)blockIdx.y * total + tok0;
-  uint32_t gt = 0, eq = 0;
-  for (int i = begin + threadIdx.x; i < end; i += SEL_THREADS) {
-    const uint32_t key = float_to_ordered(row[i]);
-    gt += key > tau;
-    eq += key == tau;
+  const int begin = max(blockIdx.x * SEL_PER_BLOCK, floor_rank);   // ranks below the floor do not compete
+  const bool active = begin < n && begin < (int)(blockIdx.x + 1) * SEL_PER_BLOCK;   // uniform in the workgroup
+  if (active) {
+    const int end = min(n, (int)(blockIdx.x + 1) * SEL_PER_BLOCK);
+    for (int i = threadIdx.x; i < SEL_BINS; i += SEL_THREADS) lh[i] = 0;
+    __syncthreads();
+    const uint32_t want_hi = pass == 0 ? 0u : (pass == 1 ? state[b].prefix >> 21 : state[b].prefix >> 10);
+    const float* row = I + (size_t)blockIdx.y * total + tok0;
+    for (int i = begin + threadIdx.x; i < end; i += SEL_THREADS) {
+      uint32_t digit, hi;
+      digit_of(pass, float_to_ordered(row[i]), &digit, &hi);
+      if (hi == want_hi) atomicAdd(&lh[digit], 1u);
+    }
+    __syncthreads();
+    uint32_t* gh = hist + ((size_t)b * 3 + pass) * SEL_BINS;
+    for (int i = threadIdx.x; i < SEL_BINS; i += SEL_THREADS)
+      if (lh[i]) atomicAdd(&gh[i], lh[i]);
   }
-  for (int off = 32; off >= 1; off >>= 1) { gt += __shfl_xor(gt, off); eq += __shfl_xor(eq, off); }
-  if ((threadIdx.x & 63) == 0) { atomicAdd(&sh[0], gt); atomicAdd(&sh[1], eq); }
-  __syncthreads();
-  if (threadIdx.x < 2 && sh[threadIdx.x])
-    atomicAdd(&counts[((size_t)b * layers + blockIdx.y) * 2 + threadIdx.x], sh[threadIdx.x]);
+  // every workgroup of the sequence takes a ticket, the idle ones included
+  if (last_workgroup(tickets, pass, seq.batch, b))
+    find_digit(pass, b, hist, state);
 }
 
-// One thread per sequence.  The retained total of a sequence is its budget (known
-// on the host), so every thread derives its own first offset from the table.
-__global__ void select_finalize(SeqTable seq, int layers, int floor_rank, BudgetTable budget,
-                                const SelState* __restrict__ state,
-                                const uint32_t* __restrict__ counts, float* tau,
-                                int32_t* lengths, int64_t* offsets) {
-  const int b = blockIdx.x * blockDim.x + threadIdx.x;
-  if (b >= seq.batch) return;
+// Lengths and offsets of sequence b from its per-row counts, by one workgroup.
+// The retained total of a sequence is its budget (known on the host), so the first
+// offset of every sequence comes from the table.  Ties at the threshold go to the
+// rows in ascending order until the budget is met: row l takes
+// min(eq_l, max(0, ties - sum of eq over the rows before it)).  AGENT: counts are
+// read with device-scope loads (inside the kernel that accumulated them).
+template <bool AGENT>
+__device__ __forceinline__ void finalize_sequence(int b, const SeqTable& seq, int layers,
+                                                  int floor_rank, const BudgetTable& budget,
+                                                  const SelState* state, const uint32_t* counts,
+                                                  float* tau, int32_t* lengths, int64_t* offsets) {
   int64_t off = 0;       // rows retained by the sequences before mine
   for (int p = 0; p < b; ++p) {
     const int n_p = seq.cu[p + 1] - seq.cu[p];
@@ -153,28 +204,82 @@ __global__ void select_finalize(SeqTable seq, int layers, int floor_rank, Budget
   const int64_t want = budget.b[b];
   const int n_b = seq.cu[b + 1] - seq.cu[b];
   const int64_t kept_first = floor_rank < n_b ? floor_rank : n_b;   // the floor entries
-  if (tau) tau[b] = want > 0 ? ordered_to_float(state[b].prefix) : __builtin_inff();
-  int64_t above = 0;
+  const int t = threadIdx.x;
+  if (tau && t == 0) tau[b] = want > 0 ? ordered_to_float(state[b].prefix) : __builtin_inff();
+  auto count_at = [&](size_t i) -> uint64_t { return AGENT ? load_agent(&counts[i]) : counts[i]; };
+  uint64_t above_mine = 0;
   if (want > 0)
-    for (int l = 0; l < layers; ++l) above += counts[((size_t)b * layers + l) * 2];
-  int64_t ties_left = want - above;
-  for (int l = 0; l < layers; ++l) {
-    int64_t len = kept_first;
-    if (want > 0) {
-      const int64_t gt = counts[((size_t)b * layers + l) * 2];
-      const int64_t eq = counts[((size_t)b * layers + l) * 2 + 1];
-      const int64_t take = eq < ties_left ? eq : ties_left;
-      ties_left -= take;
-      len += gt + take;
+    for (int l = t; l < layers; l += SEL_THREADS) above_mine += count_at(((size_t)b * layers + l) * 2);
+  uint64_t above;
+  block_scan_incl(above_mine, &above);
+  const int64_t ties = want - (int64_t)above;
+  uint64_t eq_before = 0, len_before = 0;      // carried over the chunks of SEL_THREADS rows
+  for (int l0 = 0; l0 < layers; l0 += SEL_THREADS) {
+    const int l = l0 + t;
+    const bool live = l < layers;
+    uint64_t gt = 0, eq = 0;
+    if (live && want > 0) {
+      gt = count_at(((size_t)b * layers + l) * 2);
+      eq = count_at(((size_t)b * layers + l) * 2 + 1);
     }
-    lengths[b * layers + l] = (int32_t)len;
-    offsets[b * layers + l] = off;
-    off += len;
+    uint64_t eq_chunk, len_chunk;
+    const uint64_t eq_excl = eq_before + block_scan_incl(eq, &eq_chunk) - eq;
+    int64_t take = ties - (int64_t)eq_excl;
+    take = take < 0 ? 0 : (take > (int64_t)eq ? (int64_t)eq : take);
+    const uint64_t len = live ? uint64_t(kept_first) + gt + uint64_t(take) : 0;
+    const uint64_t len_excl = len_before + block_scan_incl(len, &len_chunk) - len;
+    if (live) {
+      lengths[b * layers + l] = (int32_t)len;
+      offsets[b * layers + l] = off + (int64_t)len_excl;
+    }
+    eq_before += eq_chunk;
+    len_before += len_chunk;
   }
-  if (b == seq.batch - 1) offsets[seq.batch * layers] = off;
+  if (b == seq.batch - 1 && t == 0) offsets[seq.batch * layers] = off + (int64_t)len_before;
 }
 
-struct SelectLayout { size_t off_hist, off_counts, off_state, total; int words; };
+// grid: (token blocks, layers, batch): counts[b][l] = {#(I > tau), #(I == tau)}; the
+// last workgroup of a sequence then writes its lengths and offsets.
+__global__ __launch_bounds__(SEL_THREADS) void select_count(
+    const float* __restrict__ I, SeqTable seq, int total, int layers, int floor_rank,
+    BudgetTable budget, const SelState* __restrict__ state, uint32_t* __restrict__ counts,
+    uint32_t* __restrict__ tickets, float* tau, int32_t* lengths, int64_t* offsets) {
+  __shared__ uint32_t sh[2];
+  const int b = blockIdx.z;
+  const int tok0 = seq.cu[b], n = seq.cu[b + 1] - tok0;
+  const int begin = max(blockIdx.x * SEL_PER_BLOCK, floor_rank);
+  const bool active = begin < n && begin < (int)(blockIdx.x + 1) * SEL_PER_BLOCK;   // uniform in the workgroup
+  if (active) {
+    const int end = min(n, (int)(blockIdx.x + 1) * SEL_PER_BLOCK);
+    if (threadIdx.x < 2) sh[threadIdx.x] = 0;
+    __syncthreads();
+    const uint32_t tau_key = state[b].prefix;
+    const float* row = I + (size_t)blockIdx.y * total + tok0;
+    uint32_t gt = 0, eq = 0;
+    for (int i = begin + threadIdx.x; i < end; i += SEL_THREADS) {
+      const uint32_t key = float_to_ordered(row[i]);
+      gt += key > tau_key;
+      eq += key == tau_key;
+    }
+    for (int off = 32; off >= 1; off >>= 1) { gt += __shfl_xor(gt, off); eq += __shfl_xor(eq, off); }
+    if ((threadIdx.x & 63) == 0) { atomicAdd(&sh[0], gt); atomicAdd(&sh[1], eq); }
+    __syncthreads();
+    if (threadIdx.x < 2 && sh[threadIdx.x])
+      atomicAdd(&counts[((size_t)b * layers + blockIdx.y) * 2 + threadIdx.x], sh[threadIdx.x]);
+  }
+  if (last_workgroup(tickets, 3, seq.batch, b))
+    finalize_sequence<true>(b, seq, layers, floor_rank, budget, state, counts, tau, lengths, offsets);
+}
+
+// Batches whose sequences are all empty launch nothing else.  grid: (batch)
+__global__ __launch_bounds__(SEL_THREADS) void select_finalize(
+    SeqTable seq, int layers, int floor_rank, BudgetTable budget,
+    const SelState* __restrict__ state, const uint32_t* __restrict__ counts, float* tau,
+    int32_t* lengths, int64_t* offsets) {
+  finalize_sequence<false>(blockIdx.x, seq, layers, floor_rank, budget, state, counts, tau, lengths, offsets);
+}
+
+struct SelectLayout { size_t off_hist, off_counts, off_tickets, off_state, total; int words; };
 
 SelectLayout select_layout(const Problem& pb) {
   SelectLayout L{};
@@ -183,7 +288,11 @@ SelectLayout select_layout(const Problem& pb) {
   const size_t count_words = size_t(pb.batch) * pb.sel_rows * 2;
   L.off_hist = cur;   cur += hist_words * 4;
   L.off_counts = cur; cur += align_up(count_words * 4);
-  L.words = int((cur) / 4);                   // hist and counts are zeroed together
+  // 3 passes + the count sweep, each with one counter line per group of workgroups + 1
+  const size_t sel_blocks = size_t((pb.max_seqlen + SEL_PER_BLOCK - 1) / SEL_PER_BLOCK) * pb.sel_rows;
+  const size_t sel_groups = (sel_blocks + SEL_GROUP - 1) / SEL_GROUP;
+  L.off_tickets = cur; cur += align_up(4 * size_t(pb.batch) * (sel_groups + 1) * SEL_TICKET_WORDS * 4);
+  L.words = int((cur) / 4);                   // hist, counts and tickets are zeroed together
   L.off_state = cur;  cur += align_up(size_t(pb.batch) * sizeof(SelState));
   L.total = cur;
   return L;
@@ -200,6 +309,7 @@ kvc_status launch_global_select(const Problem& pb, const float* I, const int64_t
   char* w = static_cast<char*>(ws);
   uint32_t* hist = reinterpret_cast<uint32_t*>(w + L.off_hist);
   uint32_t* counts = reinterpret_cast<uint32_t*>(w + L.off_counts);
+  uint32_t* tickets = reinterpret_cast<uint32_t*>(w + L.off_tickets);
   SelState* state = reinterpret_cast<SelState*>(w + L.off_state);
   const int rows = pb.sel_rows, floor_rank = pb.min_per_layer;
   BudgetTable bt{};   // what is left to compete for after the floor entries
@@ -212,14 +322,14 @@ kvc_status launch_global_select(const Problem& pb, const float* I, const int64_t
   KVC_LAUNCH("select_init", stream, select_init<<<(L.words + 255) / 256, 256, 0, stream>>>(hist, L.words, state, bt, pb.batch));
   if (pb.max_seqlen > 0) {
     dim3 grid((unsigned)((pb.max_seqlen + SEL_PER_BLOCK - 1) / SEL_PER_BLOCK), rows, pb.batch);
-    for (int pass = 0; pass < 3; ++pass) {
-      KVC_LAUNCH("select_hist", stream, select_hist<<<grid, SEL_THREADS, 0, stream>>>(I, pb.seq, total, pass, floor_rank, state, hist));
-      KVC_LAUNCH("select_find", stream, select_find<<<pb.batch, SEL_THREADS, 0, stream>>>(pass, hist, state));
-    }
-    KVC_LAUNCH("select_count", stream, select_count<<<grid, SEL_THREADS, 0, stream>>>(I, pb.seq, total, rows, floor_rank, state, counts));
+    for (int pass = 0; pass < 3; ++pass)
+      KVC_LAUNCH("select_hist", stream, select_hist<<<grid, SEL_THREADS, 0, stream>>>(I, pb.seq, total, pass, floor_rank, state, hist, tickets));
+    KVC_LAUNCH("select_count", stream, select_count<<<grid, SEL_THREADS, 0, stream>>>(I, pb.seq, total, rows, floor_rank, bt, state, counts,
+                                                                                     tickets, tau, lengths, offsets));
+  } else {
+    KVC_LAUNCH("select_finalize", stream, select_finalize<<<pb.batch, SEL_THREADS, 0, stream>>>(pb.seq, rows, floor_rank, bt, state, counts, tau,
+                                          lengths, offsets));
   }
-  KVC_LAUNCH("select_finalize", stream, select_finalize<<<1, 64, 0, stream>>>(pb.seq, rows, floor_rank, bt, state, counts, tau,
-                                        lengths, offsets));
   return KVC_OK;
 }
 
