@@ -98,6 +98,7 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--n", type=int, default=None, help="override context length (debug)")
     ap.add_argument("--layers", type=int, default=None, help="override layer count (debug)")
+    ap.add_argument("--batch", type=int, default=None, help="override number of sequences (debug)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=8)
     ap.add_argument("--workers", type=int, default=min(16, os.cpu_count() or 1))
@@ -132,6 +133,8 @@ def main():
         over["n"] = args.n
     if args.layers:
         over["layers"] = args.layers
+    if args.batch:
+        over["batch"] = args.batch
     cfg = wl.get_config(args.config, **over)
     lens = wl.seq_lens(cfg, args.seed)
     cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
