@@ -118,7 +118,8 @@ def _rank_inputs(kind, lyr, hkv, lens, seed):
 
 
 @pytest.mark.parametrize("kind", ["scores", "ties", "signed", "constant"])
-@pytest.mark.parametrize("lens", [[1], [63], [4096], [4097], [9000, 1, 300], [20000]])
+@pytest.mark.parametrize("lens", [[1], [63], [2047], [2048, 2049], [4096], [4097], [8192, 8193],
+                                  [9000, 1, 300], [20000]])
 def test_head_rank_bit_exact(kind, lens):
     _say(f"rank {kind} lens={lens}")
     lyr, hkv = 2, 3
@@ -146,9 +147,11 @@ def test_head_rank_bit_exact(kind, lens):
 
 
 @pytest.mark.parametrize("agg_head", [kv.KVC_AGG_MEAN, kv.KVC_AGG_MAX])
-def test_composite_matches_oracle(agg_head):
-    _say(f"composite agg_head={agg_head}")
-    lyr, hkv, lens = 3, 8, [1000, 37]
+@pytest.mark.parametrize("hkv,lens", [(8, [1000, 37]), (8, [1000, 36]), (4, [512]), (3, [260, 4])])
+def test_composite_matches_oracle(agg_head, hkv, lens):
+    # 8 heads take the unrolled kernel (16-byte accesses when T is a multiple of 4), others the general one
+    _say(f"composite agg_head={agg_head} hkv={hkv} lens={lens}")
+    lyr = 3
     cu = np.concatenate([[0], np.cumsum(lens)])
     total = int(cu[-1])
     r = np.random.default_rng(5)
@@ -188,7 +191,8 @@ def _select_case(lyr, lens, budgets, kind, seed):
 @pytest.mark.parametrize("kind", ["smooth", "ties", "equal-layers"])
 @pytest.mark.parametrize("lyr,lens,fracs", [
     (4, [1024], [0.25]), (3, [5000], [0.0]), (3, [5000], [1.0]), (5, [3000, 1, 777], [0.2, 1.0, 0.5]),
-    (32, [4096], [0.1]), (2, [2049, 2048], [0.999, 0.001])])
+    (32, [4096], [0.1]), (2, [2049, 2048], [0.999, 0.001]), (128, [700, 300], [0.3, 0.6]),
+    (64, [70000], [0.15])])
 def test_global_select_bit_exact(kind, lyr, lens, fracs):
     _say(f"select {kind} lyr={lyr} lens={lens} fracs={fracs}")
     i_all, cu = _select_case(lyr, lens, fracs, kind, lyr)

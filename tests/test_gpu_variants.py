@@ -103,9 +103,10 @@ def test_global_select_floor_bit_exact(kind, lyr, lens, fracs, floor):
 # --------------------------------------------------- unstructured selection
 @pytest.mark.parametrize("kind", ["smooth", "ties"])
 @pytest.mark.parametrize("floor", [0, 5])
-def test_unstructured_select_bit_exact(kind, floor):
-    lyr, hkv, lens, fracs = 3, 4, [1500, 70], [0.3, 0.6]
-    _say(f"unstructured select {kind} floor={floor}")
+@pytest.mark.parametrize("lyr,hkv", [(3, 4), (75, 8)])      # 600 rows: several chunks of the bookkeeping scan
+def test_unstructured_select_bit_exact(kind, floor, lyr, hkv):
+    lens, fracs = [1500, 70], [0.3, 0.6]
+    _say(f"unstructured select {kind} floor={floor} rows={lyr * hkv}")
     rows = lyr * hkv
     s_sorted, cu = _select_case(rows, lens, fracs, kind, 7)          # rows = (layer, head)
     budgets = [max(int(f * rows * n), rows * min(floor, n)) for f, n in zip(fracs, lens)]
