@@ -26,7 +26,7 @@ PEAK_FP32_VALU_TFLOPS = 157.3   # 256 CUs x 4 SIMDs x 64 lanes x 2 flops x 2.4 G
 # HBM bytes per layer of the score kernels at the config-2 layer shape (32/8 heads, d=128,
 # N=131072, M=64), from rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by the copy-probe factors
 # (2.000 / 1.000); source: profiles/score_mfma_config2_hbm_traffic.md
-MEASURED_TRAFFIC_BYTES = {"score_mfma<stats>": 275.8e6, "score_mfma<emit>": 279.1e6}
+MEASURED_TRAFFIC_BYTES = {"score_mfma<stats>": 274.3e6, "score_mfma<emit>": 277.5e6}
 
 
 def log(msg):
