@@ -3,7 +3,9 @@
 
 One "step" is one kvc_compress call (score -> head-rank -> composite -> global
 select -> gather) over a synthetic Llama-3-8B-shaped bf16 cache that is already
-resident in HBM.  Prints ONE JSON line ("Measurement").
+resident in HBM.  Prints ONE JSON line: throughput in context tokens per second,
+the roofline figures of the longest-running kernel (from HIP events the library
+records on the launch stream) and the CPU oracle timed on a bounded sample.
 """
 from __future__ import annotations
 
