@@ -70,6 +70,14 @@ def lib() -> C.CDLL:
         if not os.path.exists(path):
             raise ImportError(f"{path} not found: build it with "
                               "`python -m paper_2509_05165_amd.build` (no fallback exists)")
+        # PyTorch ships its own copy of the HIP runtime.  If libkvc.so were loaded
+        # first it would pull in the system copy, and kernels launched through one
+        # copy on memory allocated through the other fail with "no ROCm-capable
+        # device is detected": make torch's copy the one this process uses.
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = C.CDLL(path)
         L.kvc_version.restype = C.c_int
         L.kvc_status_string.restype = C.c_char_p
