@@ -249,7 +249,7 @@ __global__ __launch_bounds__(256) void score_merge_few(SeqTable seq, int rows_pe
 // is a layer: both pointers advance by layer_stride floats per layer (one launch
 // can finish all layers when they were emitted in place).
 //
-// vnorm (may be null): [hkv, total] weights ||V[h,c,:]|| of this layer; the
+// vnorm (may be null): [layers][hkv, total] weights ||V[h,c,:]||; the
 // weighted attention matrix of the value-norm appendix scales every entry of
 // column c of head h by the same non-negative number, which commutes with the
 // max / mean over task tokens and over the group, so it is applied here.
@@ -302,6 +302,7 @@ __global__ void score_finish(const float* part, FinishArgs a, SeqTable seq, floa
   if (c >= total) return;
   part += blockIdx.y * part_layer_stride;
   S += blockIdx.y * layer_stride;
+  if (vnorm) vnorm += blockIdx.y * ((size_t)hkv * total);   // [layer][hkv, total]
   if (a.keep_first > 0 || a.keep_last > 0) {
     int b = 0;
     while (b + 1 < seq.batch && seq.cu[b + 1] <= c) ++b;          // sequence of token c
@@ -360,40 +361,52 @@ __global__ __launch_bounds__(256) void score_finish_plain(const float* part, flo
 }
 
 // ---------------------------------------------------------------------------
-// value norms of one layer: w[h, c] = ||V[h, c, :]||_2 in fp32.  A group of
+// value norms: w[l][h, c] = ||V_l[h, c, :]||_2 in fp32 for every layer of the table.  A group of
 // 16 lanes squares and sums one row (16 bytes per lane and step), four rows
 // per wave instruction.
 // ---------------------------------------------------------------------------
+constexpr int VN_ROWS = 4;   // rows per 16-lane group: four independent loads in flight per lane
 template <typename T>
-__global__ __launch_bounds__(256) void value_norm_kernel(const T* __restrict__ v, size_t rows,
-                                                         int d, float* __restrict__ w) {
+__global__ __launch_bounds__(256) void value_norm_kernel(PtrTable v_tab, size_t rows, int d,
+                                                         float* __restrict__ w) {
   constexpr int PER = 16 / sizeof(T);          // elements per 16-byte piece
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  // blockIdx.y = entry of the pointer table (a layer); its weights follow those of the one before
+  const T* __restrict__ v = static_cast<const T*>(v_tab.p[blockIdx.y]);
+  w += (size_t)blockIdx.y * rows;
   const int sub = threadIdx.x & 15;
-  const size_t row = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) >> 4;
-  float acc = 0.f;
-  if (row < rows) {
-    const T* p = v + row * d;
-    for (int j = sub * PER; j < d; j += 16 * PER) {
-      const uint4 raw = *reinterpret_cast<const uint4*>(p + j);
-      if (sizeof(T) == 2) {
-        const uint32_t u[4] = {raw.x, raw.y, raw.z, raw.w};
+  const size_t row0 = (((size_t)blockIdx.x * blockDim.x + threadIdx.x) >> 4) * VN_ROWS;
+  float acc[VN_ROWS];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const float lo = __uint_as_float(u[i] << 16), hi = __uint_as_float(u[i] & 0xffff0000u);
-          acc = fmaf(lo, lo, acc);
-          acc = fmaf(hi, hi, acc);
+  for (int i = 0; i < VN_ROWS; ++i) acc[i] = 0.f;
+  for (int j = sub * PER; j < d; j += 16 * PER) {
+    u32x4 raw[VN_ROWS];
+#pragma unroll
+    for (int i = 0; i < VN_ROWS; ++i) {        // V is read once: streaming loads
+      const size_t row = row0 + i < rows ? row0 + i : rows - 1;   // clamped, result dropped below
+      raw[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(v + row * d + j));
+    }
+#pragma unroll
+    for (int i = 0; i < VN_ROWS; ++i) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        if (sizeof(T) == 2) {
+          const float lo = __uint_as_float(raw[i][e] << 16), hi = __uint_as_float(raw[i][e] & 0xffff0000u);
+          acc[i] = fmaf(lo, lo, acc[i]);
+          acc[i] = fmaf(hi, hi, acc[i]);
+        } else {
+          const float f = __uint_as_float(raw[i][e]);
+          acc[i] = fmaf(f, f, acc[i]);
         }
-      } else {
-        const float f[4] = {__uint_as_float(raw.x), __uint_as_float(raw.y), __uint_as_float(raw.z),
-                            __uint_as_float(raw.w)};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) acc = fmaf(f[i], f[i], acc);
       }
     }
   }
 #pragma unroll
-  for (int off = 8; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
-  if (row < rows && sub == 0) w[row] = sqrtf(acc);
+  for (int i = 0; i < VN_ROWS; ++i) {
+#pragma unroll
+    for (int off = 8; off >= 1; off >>= 1) acc[i] += __shfl_xor(acc[i], off);
+    if (row0 + i < rows && sub == 0) w[row0 + i] = sqrtf(acc[i]);
+  }
 }
 
 
@@ -437,7 +450,7 @@ ScoreLayout score_layout(const Problem& pb) {
   L.part_layer = size_t(L.row_chunks) * pb.hkv * size_t(pb.total);
   if (L.row_chunks > 1 || pb.hkv > 8) cur += align_up(L.part_layer * L.layers_held * 4);
   L.off_vnorm = cur;
-  if (pb.value_norm) cur += align_up(size_t(pb.hkv) * size_t(pb.total) * 4);   // one layer's weights
+  if (pb.value_norm) cur += align_up(size_t(L.layers_held) * pb.hkv * size_t(pb.total) * 4);
   L.total = cur;
   return L;
 }
@@ -514,15 +527,15 @@ kvc_status launch_score(const Problem& pb, const void* const* q, const void* con
     }
 #undef KVC_SCORE_MFMA_WQ
 #undef KVC_SCORE_MFMA
-    if (vnorm) {   // one buffer of value norms: layer by layer
-      for (int l = 0; l < pb.layers; ++l) {
-        const size_t rows = size_t(pb.hkv) * total;
-        const unsigned blocks = unsigned((rows * 16 + 255) / 256);
-        KVC_LAUNCH("value_norm_kernel", stream, value_norm_kernel<uint16_t><<<blocks, 256, 0, stream>>>(
-            static_cast<const uint16_t*>(v[l]), rows, pb.d, vnorm));
-        KVC_LAUNCH("score_finish", stream, score_finish<<<(total + 255) / 256, 256, 0, stream>>>(
-            part_all + size_t(l) * out_stride, fa, pb.seq, S + size_t(l) * pb.hkv * total, 0, 0, vnorm));
-      }
+    if (vnorm && pb.layers > 0 && total > 0) {   // value norms and finish of all layers, one launch each
+      PtrTable vt{};
+      for (int l = 0; l < pb.layers; ++l) vt.p[l] = v[l];
+      const size_t rows = size_t(pb.hkv) * total;
+      const dim3 vgrid(unsigned((rows + 16 * VN_ROWS - 1) / (16 * VN_ROWS)), pb.layers);
+      KVC_LAUNCH("value_norm_kernel", stream, value_norm_kernel<uint16_t><<<vgrid, 256, 0, stream>>>(
+          vt, rows, pb.d, vnorm));
+      KVC_LAUNCH("score_finish", stream, score_finish<<<dim3((total + 255) / 256, pb.layers), 256, 0, stream>>>(
+          part_all, fa, pb.seq, S, out_stride, rows, vnorm));
     } else if (pb.layers > 0 && total > 0) {
       const bool plain = L.row_chunks == 1 && pb.keep_first == 0 && pb.keep_last == 0 &&
                          (pb.hkv == 8 || pb.hkv == 4);
@@ -583,13 +596,15 @@ kvc_status launch_score(const Problem& pb, const void* const* q, const void* con
     // before the next one reuses them
     if (vnorm) {
       const size_t rows = size_t(pb.hkv) * total;
-      const unsigned blocks = unsigned((rows * 16 + 255) / 256);
+      const unsigned blocks = unsigned((rows + 16 * VN_ROWS - 1) / (16 * VN_ROWS));
+      PtrTable vt{};
+      vt.p[0] = v[l];                       // one layer at a time on this path
       if (pb.dtype == KVC_BF16)
         KVC_LAUNCH("value_norm_kernel", stream, value_norm_kernel<uint16_t><<<blocks, 256, 0, stream>>>(
-            static_cast<const uint16_t*>(v[l]), rows, pb.d, vnorm));
+            vt, rows, pb.d, vnorm));
       else
         KVC_LAUNCH("value_norm_kernel", stream, value_norm_kernel<float><<<blocks, 256, 0, stream>>>(
-            static_cast<const float*>(v[l]), rows, pb.d, vnorm));
+            vt, rows, pb.d, vnorm));
     }
     if (per_layer_finish)
       KVC_LAUNCH("score_finish", stream, score_finish<<<(total + 255) / 256, 256, 0, stream>>>(
