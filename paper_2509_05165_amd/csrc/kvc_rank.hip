@@ -412,6 +412,12 @@ kvc_status launch_composite(const Problem& pb, const float* S_sorted, float* I,
   } else if (pb.hkv == 8) {
     dim3 grid((unsigned)((total + 255) / 256), pb.layers);
     KVC_LAUNCH("composite_kernel", stream, composite_plain<8, 1><<<grid, 256, 0, stream>>>(S_sorted, total, head_max, I));
+  } else if (pb.hkv == 4 && vec4) {
+    dim3 grid((unsigned)((total / 4 + 255) / 256), pb.layers);
+    KVC_LAUNCH("composite_kernel", stream, composite_plain<4, 4><<<grid, 256, 0, stream>>>(S_sorted, total, head_max, I));
+  } else if (pb.hkv == 4) {
+    dim3 grid((unsigned)((total + 255) / 256), pb.layers);
+    KVC_LAUNCH("composite_kernel", stream, composite_plain<4, 1><<<grid, 256, 0, stream>>>(S_sorted, total, head_max, I));
   } else {
     dim3 grid((unsigned)((total + 255) / 256), pb.layers);
     KVC_LAUNCH("composite_kernel", stream, composite_kernel<<<grid, 256, 0, stream>>>(S_sorted, pb.hkv, total, head_max, I));

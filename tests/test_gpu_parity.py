@@ -147,7 +147,7 @@ def test_head_rank_bit_exact(kind, lens):
 
 
 @pytest.mark.parametrize("agg_head", [kv.KVC_AGG_MEAN, kv.KVC_AGG_MAX])
-@pytest.mark.parametrize("hkv,lens", [(8, [1000, 37]), (8, [1000, 36]), (4, [512]), (3, [260, 4])])
+@pytest.mark.parametrize("hkv,lens", [(8, [1000, 37]), (8, [1000, 36]), (4, [512]), (4, [509]), (3, [260, 4])])
 def test_composite_matches_oracle(agg_head, hkv, lens):
     # 8 heads take the unrolled kernel (16-byte accesses when T is a multiple of 4), others the general one
     _say(f"composite agg_head={agg_head} hkv={hkv} lens={lens}")
