@@ -27,7 +27,7 @@ namespace {
 
 constexpr int SEL_BINS = 2048;
 constexpr int SEL_THREADS = 256;
-constexpr int SEL_PER_BLOCK = SEL_THREADS * 8;
+constexpr int SEL_PER_BLOCK = SEL_THREADS * 8;   // fewest elements of a row per workgroup
 
 struct SelState {
   uint32_t prefix;       // bits of the threshold key fixed so far
@@ -156,24 +156,48 @@ __device__ __forceinline__ void find_digit(int pass, int b, const uint32_t* __re
 
 // grid: (token blocks, layers, batch)
 __global__ __launch_bounds__(SEL_THREADS) void select_hist(
-    const float* __restrict__ I, SeqTable seq, int total, int pass, int floor_rank,
+    const float* __restrict__ I, SeqTable seq, int total, int pass, int floor_rank, int per_block,
     SelState* state, uint32_t* __restrict__ hist /* [batch][3][SEL_BINS] */,
     uint32_t* __restrict__ tickets) {
   __shared__ uint32_t lh[SEL_BINS];
   const int b = blockIdx.z;
   const int tok0 = seq.cu[b], n = seq.cu[b + 1] - tok0;
-  const int begin = max(blockIdx.x * SEL_PER_BLOCK, floor_rank);   // ranks below the floor do not compete
-  const bool active = begin < n && begin < (int)(blockIdx.x + 1) * SEL_PER_BLOCK;   // uniform in the workgroup
+  const int begin = max((int)blockIdx.x * per_block, floor_rank);   // ranks below the floor do not compete
+  const bool active = begin < n && begin < (int)(blockIdx.x + 1) * per_block;   // uniform in the workgroup
   if (active) {
-    const int end = min(n, (int)(blockIdx.x + 1) * SEL_PER_BLOCK);
+    const int end = min(n, (int)(blockIdx.x + 1) * per_block);
     for (int i = threadIdx.x; i < SEL_BINS; i += SEL_THREADS) lh[i] = 0;
     __syncthreads();
     const uint32_t want_hi = pass == 0 ? 0u : (pass == 1 ? state[b].prefix >> 21 : state[b].prefix >> 10);
     const float* row = I + (size_t)blockIdx.y * total + tok0;
-    for (int i = begin + threadIdx.x; i < end; i += SEL_THREADS) {
-      uint32_t digit, hi;
-      digit_of(pass, float_to_ordered(row[i]), &digit, &hi);
-      if (hi == want_hi) atomicAdd(&lh[digit], 1u);
+    // Four loads in flight per thread.  Rows are usually sorted, so the 64 elements of
+    // a wave step mostly share one digit: then one lane adds the whole count instead
+    // of 64 atomics on one address.
+    const int lane = threadIdx.x & 63;
+    for (int i0 = begin; i0 < end; i0 += SEL_THREADS * 4) {
+      float x[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int i = i0 + e * SEL_THREADS + (int)threadIdx.x;
+        x[e] = row[i < end ? i : end - 1];              // clamped; dropped below
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int i = i0 + e * SEL_THREADS + (int)threadIdx.x;
+        uint32_t digit, hi;
+        digit_of(pass, float_to_ordered(x[e]), &digit, &hi);
+        const bool ok = i < end && hi == want_hi;
+        const uint64_t all = __ballot(ok);
+        if (all == 0) continue;                          // wave-uniform
+        const int leader = __ffsll((unsigned long long)all) - 1;
+        const uint32_t d0 = __builtin_amdgcn_readlane(digit, leader);
+        const uint64_t same = __ballot(ok && digit == d0);
+        if (same == all) {
+          if (lane == leader) atomicAdd(&lh[d0], (uint32_t)__popcll(all));
+        } else if (ok) {
+          atomicAdd(&lh[digit], 1u);
+        }
+      }
     }
     __syncthreads();
     uint32_t* gh = hist + ((size_t)b * 3 + pass) * SEL_BINS;
@@ -241,16 +265,16 @@ __device__ __forceinline__ void finalize_sequence(int b, const SeqTable& seq, in
 // grid: (token blocks, layers, batch): counts[b][l] = {#(I > tau), #(I == tau)}; the
 // last workgroup of a sequence then writes its lengths and offsets.
 __global__ __launch_bounds__(SEL_THREADS) void select_count(
-    const float* __restrict__ I, SeqTable seq, int total, int layers, int floor_rank,
+    const float* __restrict__ I, SeqTable seq, int total, int layers, int floor_rank, int per_block,
     BudgetTable budget, const SelState* __restrict__ state, uint32_t* __restrict__ counts,
     uint32_t* __restrict__ tickets, float* tau, int32_t* lengths, int64_t* offsets) {
   __shared__ uint32_t sh[2];
   const int b = blockIdx.z;
   const int tok0 = seq.cu[b], n = seq.cu[b + 1] - tok0;
-  const int begin = max(blockIdx.x * SEL_PER_BLOCK, floor_rank);
-  const bool active = begin < n && begin < (int)(blockIdx.x + 1) * SEL_PER_BLOCK;   // uniform in the workgroup
+  const int begin = max((int)blockIdx.x * per_block, floor_rank);
+  const bool active = begin < n && begin < (int)(blockIdx.x + 1) * per_block;   // uniform in the workgroup
   if (active) {
-    const int end = min(n, (int)(blockIdx.x + 1) * SEL_PER_BLOCK);
+    const int end = min(n, (int)(blockIdx.x + 1) * per_block);
     if (threadIdx.x < 2) sh[threadIdx.x] = 0;
     __syncthreads();
     const uint32_t tau_key = state[b].prefix;
@@ -279,6 +303,15 @@ __global__ __launch_bounds__(SEL_THREADS) void select_finalize(
   finalize_sequence<false>(blockIdx.x, seq, layers, floor_rank, budget, state, counts, tau, lengths, offsets);
 }
 
+// Elements of a row per workgroup: every workgroup clears and flushes a 2048-bin
+// histogram, so big pools (many rows) get longer stretches per workgroup, about
+// 4096 workgroups per sequence at most.
+inline int select_per_block(const Problem& pb) {
+  int per = SEL_PER_BLOCK;
+  while (per < (1 << 20) && ((pb.max_seqlen + per - 1) / per) * int64_t(pb.sel_rows) > 4096) per *= 2;
+  return per;
+}
+
 struct SelectLayout { size_t off_hist, off_counts, off_tickets, off_state, total; int words; };
 
 SelectLayout select_layout(const Problem& pb) {
@@ -289,6 +322,8 @@ SelectLayout select_layout(const Problem& pb) {
   L.off_hist = cur;   cur += hist_words * 4;
   L.off_counts = cur; cur += align_up(count_words * 4);
   // 3 passes + the count sweep, each with one counter line per group of workgroups + 1
+  // (sized for the shortest stretch per workgroup, so that the size never shrinks when
+  // max_seqlen grows: callers may size the workspace with an upper bound)
   const size_t sel_blocks = size_t((pb.max_seqlen + SEL_PER_BLOCK - 1) / SEL_PER_BLOCK) * pb.sel_rows;
   const size_t sel_groups = (sel_blocks + SEL_GROUP - 1) / SEL_GROUP;
   L.off_tickets = cur; cur += align_up(4 * size_t(pb.batch) * (sel_groups + 1) * SEL_TICKET_WORDS * 4);
@@ -321,10 +356,11 @@ kvc_status launch_global_select(const Problem& pb, const float* I, const int64_t
 
   KVC_LAUNCH("select_init", stream, select_init<<<(L.words + 255) / 256, 256, 0, stream>>>(hist, L.words, state, bt, pb.batch));
   if (pb.max_seqlen > 0) {
-    dim3 grid((unsigned)((pb.max_seqlen + SEL_PER_BLOCK - 1) / SEL_PER_BLOCK), rows, pb.batch);
+    const int per_block = select_per_block(pb);
+    dim3 grid((unsigned)((pb.max_seqlen + per_block - 1) / per_block), rows, pb.batch);
     for (int pass = 0; pass < 3; ++pass)
-      KVC_LAUNCH("select_hist", stream, select_hist<<<grid, SEL_THREADS, 0, stream>>>(I, pb.seq, total, pass, floor_rank, state, hist, tickets));
-    KVC_LAUNCH("select_count", stream, select_count<<<grid, SEL_THREADS, 0, stream>>>(I, pb.seq, total, rows, floor_rank, bt, state, counts,
+      KVC_LAUNCH("select_hist", stream, select_hist<<<grid, SEL_THREADS, 0, stream>>>(I, pb.seq, total, pass, floor_rank, per_block, state, hist, tickets));
+    KVC_LAUNCH("select_count", stream, select_count<<<grid, SEL_THREADS, 0, stream>>>(I, pb.seq, total, rows, floor_rank, per_block, bt, state, counts,
                                                                                      tickets, tau, lengths, offsets));
   } else {
     KVC_LAUNCH("select_finalize", stream, select_finalize<<<pb.batch, SEL_THREADS, 0, stream>>>(pb.seq, rows, floor_rank, bt, state, counts, tau,
