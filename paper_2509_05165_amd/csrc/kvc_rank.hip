@@ -61,19 +61,22 @@ __device__ __forceinline__ void lds_barrier() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-// lanes (among `valid`) whose 8-bit digit equals mine.  Per bit: the lanes that
-// agree with my bit are ~(ballot ^ mine), with `mine` all ones or all zeros;
-// written on 32-bit halves as x & ~(y ^ z), which is one three-input bit
-// operation per half.
-__device__ __forceinline__ uint64_t match_digit(uint32_t digit, uint64_t valid) {
+// lanes (among `valid`) whose 8-bit digit (bits SHIFT..SHIFT+7 of the key) equals
+// mine.  Per bit: `mine` is all ones or all zeros (one signed bit-field extract),
+// the lanes that agree with it are ~(ballot ^ mine); written on 32-bit halves as
+// x & ~(y ^ z), which is one three-input bit operation per half (truth table 0x90:
+// the encoding the compiler itself picks for that expression; spelled out because
+// it otherwise splits it into an xor and a shared three-input and).  Four vector
+// instructions per bit: extract, compare (the ballot), two bit operations.
+template <int SHIFT>
+__device__ __forceinline__ uint64_t match_digit(uint32_t key, uint64_t valid) {
   uint32_t lo = (uint32_t)valid, hi = (uint32_t)(valid >> 32);
 #pragma unroll
   for (int bit = 0; bit < 8; ++bit) {
-    const uint32_t mine = 0u - ((digit >> bit) & 1u);
+    // (spelled as the instruction: the builtin is lowered to a shift pair)
+    uint32_t mine;
+    asm("v_bfe_i32 %0, %1, %2, 1" : "=v"(mine) : "v"(key), "n"(SHIFT + bit));
     const uint64_t bal = __ballot(mine != 0u);
-    // x & ~(y ^ z) as one v_bitop3_b32 (truth table 0x90: the encoding the compiler
-    // itself picks for that expression; spelled out because it otherwise splits it
-    // into an xor and a shared three-input and)
     lo = __builtin_amdgcn_bitop3_b32(lo, (uint32_t)bal, mine, 0x90);
     hi = __builtin_amdgcn_bitop3_b32(hi, (uint32_t)(bal >> 32), mine, 0x90);
   }
@@ -173,7 +176,7 @@ __device__ __forceinline__ void radix_pass(RankShared& sh, int n, const float* _
       const bool valid = wbase + e * 64 < n;
       const uint64_t vmask = __ballot(valid);
       const uint32_t digit = (key[e] >> shift) & 255u;
-      const uint64_t mask = match_digit(digit, vmask);
+      const uint64_t mask = match_digit<shift>(key[e], vmask);
       const int below = lanes_below(mask);
       uint32_t prev = 0;
       if (valid) prev = sh.wave_cnt[wave][digit];
