@@ -227,6 +227,23 @@ kvc_status kvc_global_select(const kvc_params* params, const float* I,
                              float* tau, int32_t* lengths, int64_t* offsets,
                              void* workspace, size_t workspace_bytes, void* stream);
 
+/* kvc_global_select for callers that cannot allocate device memory or pass a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, results and errors as kvc_global_select
+ * minus the workspace: the histograms, counters and tickets live in a buffer of
+ * KVC_SELECT_STATIC_BYTES bytes that is part of the library's device image (one
+ * copy per GPU, held until the process ends).  The call allocates nothing and
+ * clears what it needs with a kernel on `stream`.  Problems whose select
+ * workspace would exceed that size (very many sequences times rows times
+ * tokens) return KVC_ERR_UNSUPPORTED with nothing enqueued.  Every call on a
+ * GPU shares that GPU's buffer: calls that may overlap on one GPU (different
+ * streams, different threads) race and must be serialised by the caller. */
+#define KVC_SELECT_STATIC_BYTES (4u << 20)
+kvc_status kvc_global_select_static(const kvc_params* params, const float* I,
+                                    const int64_t* cu_seqlens, const int64_t* budget,
+                                    float* tau, int32_t* lengths, int64_t* offsets,
+                                    void* stream);
+
 /* Stage 5, Section 3.3 final selection.  Copies rows idx[l,h,0..N_{b,l}) of
  * K and V (bit copies) into the pools; lengths/offsets are read on the device.
  * total_budget = sum_b budget[b] (host value, sizes the launch).  v and v_out

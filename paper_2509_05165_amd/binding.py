@@ -92,11 +92,12 @@ def lib() -> C.CDLL:
         L.kvc_head_rank.argtypes = [pp, vp, i64p, vp, vp, vp, C.c_size_t, vp]
         L.kvc_composite.argtypes = [pp, vp, i64p, vp, vp]
         L.kvc_global_select.argtypes = [pp, vp, i64p, i64p, vp, vp, vp, vp, C.c_size_t, vp]
+        L.kvc_global_select_static.argtypes = [pp, vp, i64p, i64p, vp, vp, vp, vp]
         L.kvc_gather.argtypes = [pp, ptab, ptab, vp, vp, vp, i64p, C.c_int64, vp, vp, vp,
                                  C.c_size_t, vp]
         L.kvc_compress.argtypes = [pp, C.POINTER(_Inputs), C.POINTER(_Outputs), vp, C.c_size_t, vp]
         for name in ("kvc_workspace_size", "kvc_score", "kvc_head_rank", "kvc_composite",
-                     "kvc_global_select", "kvc_gather", "kvc_compress"):
+                     "kvc_global_select", "kvc_global_select_static", "kvc_gather", "kvc_compress"):
             getattr(L, name).restype = C.c_int
         _LIB = L
     return _LIB
@@ -173,6 +174,12 @@ def kvc_global_select(params, I, cu_seqlens, budget, tau, lengths, offsets, work
                                    workspace_bytes, _vp(stream)), "kvc_global_select")
 
 
+def kvc_global_select_static(params, I, cu_seqlens, budget, tau, lengths, offsets, stream=0):
+    _check(lib().kvc_global_select_static(C.byref(params), _vp(I), _i64(cu_seqlens),
+                                          _i64(budget), _vp(tau), _vp(lengths), _vp(offsets),
+                                          _vp(stream)), "kvc_global_select_static")
+
+
 def kvc_gather(params, k, v, idx, lengths, offsets, cu_seqlens, total_budget, k_out, v_out,
                stream=0, workspace=0, workspace_bytes=0):
     _check(lib().kvc_gather(C.byref(params), _ptr_table(k), _ptr_table(v), _vp(idx),
@@ -226,3 +233,4 @@ def kvc_copy_probe(dst, src, nbytes: int, stream=0) -> None:
     fn.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     fn.restype = C.c_int
     _check(fn(_vp(dst), _vp(src), nbytes, _vp(stream)), "kvc_copy_probe")
+

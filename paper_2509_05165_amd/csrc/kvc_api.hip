@@ -329,6 +329,27 @@ kvc_status kvc_global_select(const kvc_params* params, const float* I,
                               static_cast<hipStream_t>(stream));
 }
 
+kvc_status kvc_global_select_static(const kvc_params* params, const float* I,
+                                    const int64_t* cu_seqlens, const int64_t* budget, float* tau,
+                                    int32_t* lengths, int64_t* offsets, void* stream) {
+  Problem pb{};
+  kvc_status st = make_problem(params, cu_seqlens, &pb);
+  if (st != KVC_OK) return st;
+  if ((st = check_budget(pb, cu_seqlens, budget, nullptr)) != KVC_OK) return st;
+  if (!lengths || !offsets) { set_error("lengths or offsets is NULL"); return KVC_ERR_INVALID_ARG; }
+  if (!I && pb.total > 0) { set_error("I is NULL"); return KVC_ERR_INVALID_ARG; }
+  const size_t need = select_workspace_bytes(pb);
+  if (need > size_t(KVC_SELECT_STATIC_BYTES)) {
+    set_error("problem needs %zu bytes of select scratch, the static buffer holds %zu", need,
+              size_t(KVC_SELECT_STATIC_BYTES));
+    return KVC_ERR_UNSUPPORTED;
+  }
+  void* scratch_ptr = nullptr;
+  if ((st = select_static_scratch(&scratch_ptr)) != KVC_OK) return st;
+  return launch_global_select(pb, I, budget, tau, lengths, offsets, scratch_ptr,
+                              static_cast<hipStream_t>(stream));
+}
+
 kvc_status kvc_gather(const kvc_params* params, const void* const* k, const void* const* v,
                       const int32_t* idx, const int32_t* lengths, const int64_t* offsets,
                       const int64_t* cu_seqlens, int64_t total_budget, void* k_out, void* v_out,

@@ -72,6 +72,10 @@ kvc_status launch_global_select(const Problem& pb, const float* I, const int64_t
                                 float* tau, int32_t* lengths, int64_t* offsets, void* ws,
                                 hipStream_t stream);
 
+// Device address of the current GPU's file-scope scratch array of the select
+// stage (KVC_SELECT_STATIC_BYTES bytes, 256-byte aligned).
+kvc_status select_static_scratch(void** ptr);
+
 size_t gather_workspace_bytes(const Problem& pb);
 kvc_status launch_gather(const Problem& pb, const void* const* k, const void* const* v,
                          const int32_t* idx, const int32_t* lengths, const int64_t* offsets,

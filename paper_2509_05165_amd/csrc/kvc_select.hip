@@ -19,11 +19,20 @@
 // unstructured variant.  With a per-row floor f the first f ranks of every row
 // are kept unconditionally and stay out of the histograms; the budget that is
 // searched for is what remains after them.
+#include <mutex>
+
 #include "kvc_internal.h"
 
 namespace kvc {
 
 namespace {
+
+// Scratch of kvc_global_select_static: the histograms, counters, tickets and
+// per-sequence state that kvc_global_select takes from the caller's workspace.
+// One copy per GPU, held until the process ends.  In host code the array's name
+// is only a stand-in for the symbol; its device address is looked up once per
+// device (static_scratch) and that pointer is what kernels receive.
+static __device__ __align__(256) unsigned char scratch[KVC_SELECT_STATIC_BYTES];
 
 constexpr int SEL_BINS = 2048;
 constexpr int SEL_THREADS = 256;
@@ -336,6 +345,31 @@ SelectLayout select_layout(const Problem& pb) {
 }  // namespace
 
 size_t select_workspace_bytes(const Problem& pb) { return select_layout(pb).total; }
+
+// Device address of this GPU's copy of `scratch` (looked up on the first call on
+// each device, with that device current).
+kvc_status select_static_scratch(void** ptr) {
+  constexpr int MAX_DEVICES = 64;
+  static std::mutex mu;
+  static void* per_device[MAX_DEVICES] = {};
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+  if (dev < 0 || dev >= MAX_DEVICES) {
+    set_error("device ordinal %d outside [0, %d)", dev, MAX_DEVICES);
+    return KVC_ERR_UNSUPPORTED;
+  }
+  std::lock_guard<std::mutex> lock(mu);
+  if (!per_device[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+    if (!p) { set_error("hipGetSymbolAddress(scratch) returned NULL"); return KVC_ERR_HIP; }
+    per_device[dev] = p;
+  }
+  *ptr = per_device[dev];
+  return KVC_OK;
+}
 
 kvc_status launch_global_select(const Problem& pb, const float* I, const int64_t* budget,
                                 float* tau, int32_t* lengths, int64_t* offsets, void* ws,

@@ -156,3 +156,17 @@ def test_variant_argument_checks_run_before_any_gpu_call():
     # position order needs workspace in the gather stage
     expect(3, kv.kvc_gather, P(order=kv.KVC_ORDER_POSITION), [FAKE] * 2, [FAKE] * 2, FAKE, FAKE, FAKE,
            cu, 5, FAKE, FAKE, 0)
+
+
+def test_static_select_rejects_what_its_buffer_cannot_hold():
+    # 64 sequences x 128 rows of 2^24 tokens need far more ticket lines than the
+    # built-in buffer holds: refused on the host, nothing enqueued
+    import numpy as np
+    lyr, bt = 128, 64
+    n = (1 << 30) // bt - 1
+    p = kv.KvcParams(bt, lyr, 8, 8, 128, 64, kv.KVC_BF16)
+    cu = [i * n for i in range(bt + 1)]
+    expect(2, kv.kvc_global_select_static, p, FAKE, cu, [0] * bt, 0, FAKE, FAKE)
+    # and the argument checks of kvc_global_select apply unchanged
+    expect(1, kv.kvc_global_select_static, P(), FAKE, [0, 100], [10 ** 9], 0, FAKE, FAKE)
+    expect(1, kv.kvc_global_select_static, P(), FAKE, [0, 100], [10], 0, 0, FAKE)
