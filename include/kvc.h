@@ -286,6 +286,28 @@ int kvc_profile_collect(kvc_profile_entry* out, int capacity);
  * byte counters are scaled against. */
 kvc_status kvc_copy_probe(void* dst, const void* src, size_t bytes, void* stream);
 
+/* Measurement aid: a bf16 MFMA loop that never leaves the registers, issued in
+ * the shape of the score kernels (v_mfma_f32_32x32x16_bf16, 512 workgroups of
+ * four waves = two waves per SIMD on 256 compute units, 16 MFMAs per wave and
+ * iteration).  What it sustains is the measured matrix-core ceiling of the GPU
+ * it runs on, under the clocks the power management grants such a load.
+ *   operands   device, KVC_MFMA_PROBE_OPERAND_BYTES bytes of bf16 values, read
+ *              once; fill them with values distributed like the workload
+ *              (matrix-core power, hence clock, depends on operand bits)
+ *   iterations > 0; mode 0: MFMAs only; mode 1: each MFMA is followed by the
+ *              vector work the statistics pass of kvc_score does per MFMA (two
+ *              scale-and-shift FMAs, two exp2, two adds)
+ *   sink       device, KVC_MFMA_PROBE_SINK_FLOATS floats, overwritten
+ *   cycles     device int64[2] or NULL: shader-clock cycles and ticks of the
+ *              constant 100 MHz counter that elapsed over the loop of one wave
+ *              (their ratio is the shader clock the loop ran at)
+ *   flops      host, or NULL: floating-point operations issued by the launch
+ * Asynchronous on `stream`; time it with events. */
+#define KVC_MFMA_PROBE_OPERAND_BYTES (24 * 256 * 16)
+#define KVC_MFMA_PROBE_SINK_FLOATS (512 * 256)
+kvc_status kvc_mfma_probe(const void* operands, int32_t iterations, int32_t mode, float* sink,
+                          int64_t* cycles, double* flops, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

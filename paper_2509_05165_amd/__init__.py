@@ -8,5 +8,6 @@ from .binding import (  # noqa: F401
     kvc_version, kvc_status_string, kvc_last_error, kvc_budget, kvc_workspace_size,
     kvc_score, kvc_head_rank, kvc_composite, kvc_global_select, kvc_global_select_static,
     kvc_gather, kvc_compress,
-    kvc_profile_enable, kvc_profile_collect, kvc_copy_probe,
+    kvc_profile_enable, kvc_profile_collect, kvc_copy_probe, kvc_mfma_probe,
+    KVC_MFMA_PROBE_OPERAND_BYTES, KVC_MFMA_PROBE_SINK_FLOATS,
 )

@@ -234,3 +234,18 @@ def kvc_copy_probe(dst, src, nbytes: int, stream=0) -> None:
     fn.restype = C.c_int
     _check(fn(_vp(dst), _vp(src), nbytes, _vp(stream)), "kvc_copy_probe")
 
+
+KVC_MFMA_PROBE_OPERAND_BYTES = 24 * 256 * 16
+KVC_MFMA_PROBE_SINK_FLOATS = 512 * 256
+
+
+def kvc_mfma_probe(operands, iterations: int, mode: int, sink, cycles=0, stream=0) -> float:
+    """Enqueues the register-resident MFMA loop; returns the flops it issues."""
+    fn = lib().kvc_mfma_probe
+    fn.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                   C.POINTER(C.c_double), C.c_void_p]
+    fn.restype = C.c_int
+    flops = C.c_double(0.0)
+    _check(fn(_vp(operands), iterations, mode, _vp(sink), _vp(cycles), C.byref(flops),
+              _vp(stream)), "kvc_mfma_probe")
+    return flops.value

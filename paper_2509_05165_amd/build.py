@@ -9,7 +9,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libkvc.so")
-SOURCES = ["kvc_api.hip", "kvc_score.hip", "kvc_rank.hip", "kvc_select.hip", "kvc_gather.hip"]
+SOURCES = ["kvc_api.hip", "kvc_score.hip", "kvc_rank.hip", "kvc_select.hip", "kvc_gather.hip",
+           "kvc_probe.hip"]
 
 
 def hipcc() -> str:

@@ -383,6 +383,16 @@ kvc_status kvc_copy_probe(void* dst, const void* src, size_t bytes, void* stream
   return launch_copy_probe(dst, src, bytes, static_cast<hipStream_t>(stream));
 }
 
+kvc_status kvc_mfma_probe(const void* operands, int32_t iterations, int32_t mode, float* sink,
+                          int64_t* cycles, double* flops, void* stream) {
+  if (!operands || !sink || iterations < 1 || (mode != 0 && mode != 1)) {
+    set_error("mfma probe needs operands, a sink, iterations >= 1 and mode 0 or 1");
+    return KVC_ERR_INVALID_ARG;
+  }
+  return launch_mfma_probe(operands, iterations, mode, sink, cycles, flops,
+                           static_cast<hipStream_t>(stream));
+}
+
 kvc_status kvc_compress(const kvc_params* params, const kvc_inputs* in, const kvc_outputs* out,
                         void* workspace, size_t workspace_bytes, void* stream) {
   if (!in || !out) { set_error("inputs or outputs is NULL"); return KVC_ERR_INVALID_ARG; }

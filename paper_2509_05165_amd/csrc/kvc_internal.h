@@ -83,6 +83,8 @@ kvc_status launch_gather(const Problem& pb, const void* const* k, const void* co
                          hipStream_t stream);
 
 kvc_status launch_copy_probe(void* dst, const void* src, size_t bytes, hipStream_t stream);
+kvc_status launch_mfma_probe(const void* operands, int iterations, int mode, float* sink,
+                             int64_t* cycles, double* flops, hipStream_t stream);
 
 // ---------------------------------------------------------------------------
 // Device helpers

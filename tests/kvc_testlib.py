@@ -37,11 +37,13 @@ class Workload:
 
     def params(self, **kw):
         c = self.cfg
+        kw.setdefault("causal_tail", c.causal_tail)
         return kv.KvcParams(c.batch, c.layers, c.hq, c.hkv, c.head_dim, c.window, self.dtype, **kw)
 
     def oracle(self, **kw):
         """Oracle result per sequence (list of dicts)."""
         out = []
+        kw.setdefault("causal_tail", bool(self.cfg.causal_tail))
         for b in range(self.cfg.batch):
             qs = [self.seq[b][l][0] for l in range(self.cfg.layers)]
             ks = [self.seq[b][l][1] for l in range(self.cfg.layers)]

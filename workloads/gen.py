@@ -52,6 +52,7 @@ class WorkloadConfig:
     needle_gain: float = 8.0
     key_lognormal_sigma: float = 0.0
     q_scale_ramp: Optional[Tuple[float, float]] = None  # (first layer, last layer)
+    causal_tail: int = 0            # 1: the window queries are the last M context tokens
 
     @property
     def group(self) -> int:
@@ -69,6 +70,17 @@ _CONFIGS = {
     # the regime of the paper's own evaluation (Section 4.1: 4096-token contexts,
     # Section 4.2: an 8B model of 32 layers, 32/8 heads): many short sequences
     5: WorkloadConfig(5, "llama3-8b-4k-b32", 32, 32, 32, 8, 128, 64, "bf16", 50, n=4096),
+    # the other two evaluated models (Section 4.2) at the same 4096-token regime:
+    # a 7B model of 28 layers with 28/4 heads (G = 7), a 14B model of 40 layers with
+    # 40/8 heads (G = 5); head size 128 in both
+    6: WorkloadConfig(6, "qwen2.5-7b-4k-b32", 32, 28, 28, 4, 128, 64, "bf16", 50, n=4096),
+    7: WorkloadConfig(7, "qwen3-14b-4k-b32", 32, 40, 40, 8, 128, 64, "bf16", 50, n=4096),
+    # task-aware setting (Sections 3.2.1-3.2.2): M is the total number of task tokens of
+    # all tasks, here 1024 against a 32k context; and the task-agnostic reading where
+    # the window queries are the last M context tokens (causal tail)
+    8: WorkloadConfig(8, "llama3-8b-32k-m1024", 1, 32, 32, 8, 128, 1024, "bf16", 20, n=32768),
+    9: WorkloadConfig(9, "llama3-8b-32k-causal-tail", 1, 32, 32, 8, 128, 64, "bf16", 20, n=32768,
+                      causal_tail=1),
 }
 
 
