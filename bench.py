@@ -137,7 +137,7 @@ class GpuSampler(threading.Thread):
 
     def __init__(self, period=0.02):
         super().__init__(daemon=True)
-        self.period, self.samples, self._stop = period, [], threading.Event()
+        self.period, self.samples, self._halt = period, [], threading.Event()
         dev = sorted(glob.glob("/sys/class/drm/card*/device"))
         self.dev = dev[0] if dev else None
         self.power_file = None
