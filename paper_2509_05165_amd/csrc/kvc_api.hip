@@ -35,13 +35,13 @@ void prof_begin(const char* name, hipStream_t stream) {
   if (!g_prof_on) return;
   ProfRec r{name, nullptr, nullptr};
   if (hipEventCreate(&r.start) != hipSuccess || hipEventCreate(&r.stop) != hipSuccess) return;
-  hipEventRecord(r.start, stream);
+  (void)hipEventRecord(r.start, stream);
   g_prof.push_back(r);
 }
 
 void prof_end(hipStream_t stream) {
   if (!g_prof_on || g_prof.empty()) return;
-  hipEventRecord(g_prof.back().stop, stream);
+  (void)hipEventRecord(g_prof.back().stop, stream);
 }
 
 static kvc_status check_params(const kvc_params* p) {
@@ -229,8 +229,8 @@ int kvc_profile_collect(kvc_profile_entry* out, int capacity) {
     if (hipEventSynchronize(r.stop) != hipSuccess ||
         hipEventElapsedTime(&ms, r.start, r.stop) != hipSuccess)
       failed = true;
-    hipEventDestroy(r.start);
-    hipEventDestroy(r.stop);
+    (void)hipEventDestroy(r.start);
+    (void)hipEventDestroy(r.stop);
     int slot = -1;
     for (int i = 0; i < count && i < capacity; ++i)
       if (std::strncmp(out[i].name, r.name, sizeof(out[i].name) - 1) == 0) { slot = i; break; }

@@ -89,6 +89,13 @@ kvc_status launch_mfma_probe(const void* operands, int iterations, int mode, flo
 // ---------------------------------------------------------------------------
 // Device helpers
 // ---------------------------------------------------------------------------
+// Wait until at most N of this wave's vector-memory operations (loads, stores,
+// atomics) are still outstanding.
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
 // Monotone map from float to unsigned: a < b  <=>  key(a) < key(b); -0 maps to
 // the same key as +0.
 __device__ __forceinline__ uint32_t float_to_ordered(float f) {

@@ -153,7 +153,7 @@ __device__ __forceinline__ void radix_pass(RankShared& sh, int n, const float* _
   KVC_RANK_LOAD_TILE(0, key, val)
   // (explicit, so that the loop body starts with no load the compiler still has to
   // wait for: see the wait before the scatter)
-  if (!LIN) __builtin_amdgcn_s_waitcnt(0x0F70);
+  if (!LIN) wait_vmcnt<0>();
 
   for (int base = 0; base < n; base += TILE) {
     // next tile's loads fly while this one is ranked and scattered
@@ -233,7 +233,7 @@ __device__ __forceinline__ void radix_pass(RankShared& sh, int n, const float* _
     // stores share one in-order counter, and left to the compiler the wait for the
     // prefetched loads lands in the next tile's ranking, behind this tile's stores.
     if (!LIN && !LOUT) {
-      __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+      wait_vmcnt<0>();
 #pragma unroll
       for (int e = 0; e < ITEMS; ++e) { key[e] = nkey[e]; val[e] = nval[e]; }
     }

@@ -45,11 +45,6 @@ __device__ __forceinline__ void lds_dma16(const void* gptr, uint32_t lds_base) {
   asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off nt" ::"s"(lds_base), "v"(gptr)
                : "memory");
 }
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-
 // Combine the two half-waves: both halves end up with op(lower, upper).
 template <bool MAX>
 __device__ __forceinline__ float cross_half(float v) {
@@ -135,38 +130,53 @@ __device__ __forceinline__ void stats_slice(int i, const f32x16& x0, const f32x1
 }
 
 // EMIT: reduce one 32x32 logit tile (queries on rows) over its 32 query rows:
-// max of t, or sum of 2^t, with t = logit*c2 - lse2.  Result in both half-waves.
-// TASK_MAX: the accumulators were started from -lse2/c2 (nl holds that), so they
-// already are t/c2; the maximum commutes with the positive factor c2, which is
-// applied once at the end instead of once per element.
+// max of t, or sum of 2^t, with t = logit*c2 - lse2 (nl holds -lse2 of the lane's 16
+// rows).  Result in both half-waves.
+//
+// MF_EMIT_RECENTRE (TASK_MAX only) is the cheaper form: the accumulators start from
+// -(lse2[row] - lse2[first row of the block])/c2 (nl holds that) instead of zero, so
+// they are (t + lse2[first row])/c2; the maximum commutes with the positive factor c2
+// and the common shift, which are applied once at the end (one FMA with base =
+// -lse2[first row]) instead of once per element.  It costs accuracy in proportion to
+// the start value: nothing while the rows of a block have similar log-sum-exps, up to
+// 2e-4 relative when they lie hundreds of units apart.  Off: every element gets its
+// own FMA and the accuracy does not depend on the data.
+#ifndef KVC_EMIT_RECENTRE
+#define KVC_EMIT_RECENTRE 0
+#endif
+constexpr bool MF_EMIT_RECENTRE = KVC_EMIT_RECENTRE != 0;
 template <bool TASK_MAX>
-__device__ __forceinline__ float emit_fold(const f32x16& acc, float c2, const float (&nl)[16]) {
+__device__ __forceinline__ float emit_fold(const f32x16& acc, float c2, const float (&nl)[16],
+                                           float base) {
   float v = TASK_MAX ? NEG_BIG : 0.f;
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
-    if (TASK_MAX) v = fmaxf(v, acc[r]);
+    if (TASK_MAX) v = fmaxf(v, MF_EMIT_RECENTRE ? acc[r] : fmaf(acc[r], c2, nl[r]));
     else v += fast_exp2(fmaf(acc[r], c2, nl[r]));
   }
   v = cross_half<TASK_MAX>(v);
-  return TASK_MAX ? v * c2 : v;
+  return (TASK_MAX && MF_EMIT_RECENTRE) ? fmaf(v, c2, base) : v;
 }
 // The same for two tiles in 16 slices: slice i handles elements 2(i%8), 2(i%8)+1 of
 // tile i/8; the cross-half combine of a tile follows its last slice.
 template <bool TASK_MAX>
 __device__ __forceinline__ void emit_slice(int i, const f32x16& x0, const f32x16& x1, float c2,
-                                           const float (&nl)[2][16], float (&v)[2]) {
+                                           const float (&nl)[2][16], const float (&base)[2],
+                                           float (&v)[2]) {
   const int b = i >> 3, r = 2 * (i & 7);
   const f32x16& x = b ? x1 : x0;
   if ((i & 7) == 0) v[b] = TASK_MAX ? NEG_BIG : 0.f;
-  if (TASK_MAX) {
+  if (TASK_MAX && MF_EMIT_RECENTRE) {
     v[b] = fmaxf(v[b], fmaxf(x[r], x[r + 1]));
+  } else if (TASK_MAX) {
+    v[b] = fmaxf(v[b], fmaxf(fmaf(x[r], c2, nl[b][r]), fmaf(x[r + 1], c2, nl[b][r + 1])));
   } else {
     const float t0 = fmaf(x[r], c2, nl[b][r]), t1 = fmaf(x[r + 1], c2, nl[b][r + 1]);
     v[b] += fast_exp2(t0) + fast_exp2(t1);
   }
   if ((i & 7) == 7) {
     v[b] = cross_half<TASK_MAX>(v[b]);
-    if (TASK_MAX) v[b] *= c2;
+    if (TASK_MAX && MF_EMIT_RECENTRE) v[b] = fmaf(v[b], c2, base[b]);
   }
 }
 
@@ -299,6 +309,7 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
   if (EMIT && (int)threadIdx.x < nqb * 32)
     my_nl = -lse2[((size_t)zid * hq + h * group) * window + row0 + threadIdx.x];
   float nl[2][16];   // EMIT: minus lse2 of the lane's accumulator rows, filled after the first barrier
+  float nbase[2] = {0.f, 0.f};   // MF_EMIT_RECENTRE: minus lse2 of the first row of each q block
 
   float mrun[2] = {NEG_BIG, NEG_BIG}, srun[2] = {0.f, 0.f};   // STATS, in log2 units
   const int bpg = window / 32;                                 // q blocks per query head
@@ -328,8 +339,8 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
   auto mfma_tile = [&](f32x16 (&a)[2], const uint4 (&kf)[8]) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      a[0][r] = (EMIT && TASK_MAX) ? nl[0][r] : 0.f;
-      a[1][r] = (EMIT && TASK_MAX) ? nl[1][r] : 0.f;
+      a[0][r] = (EMIT && TASK_MAX && MF_EMIT_RECENTRE) ? nl[0][r] : 0.f;
+      a[1][r] = (EMIT && TASK_MAX && MF_EMIT_RECENTRE) ? nl[1][r] : 0.f;
     }
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
@@ -365,8 +376,8 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
   };
   auto emit_store = [&](const f32x16 (&a)[2], int buf, int kt) {
     float v[2];
-    v[0] = emit_fold<TASK_MAX>(a[0], c2, nl[0]);
-    v[1] = emit_fold<TASK_MAX>(a[1], c2, nl[1]);
+    v[0] = emit_fold<TASK_MAX>(a[0], c2, nl[0], nbase[0]);
+    v[1] = emit_fold<TASK_MAX>(a[1], c2, nl[1], nbase[1]);
     red_store(v, buf, kt);
   };
   // EMIT: threads 0..127 turn red[buf] into the group value of one key each
@@ -486,12 +497,17 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
         nl[qb][4 * i + 0] = v.x; nl[qb][4 * i + 1] = v.y; nl[qb][4 * i + 2] = v.z; nl[qb][4 * i + 3] = v.w;
       }
     }
-    if (TASK_MAX) {   // accumulators start from -lse2/c2 (see emit_fold)
+    if (TASK_MAX && MF_EMIT_RECENTRE) {   // accumulators start from -(lse2 - lse2[first row])/c2
       const float inv_c2 = 1.f / c2;
 #pragma unroll
-      for (int qb = 0; qb < 2; ++qb)
+      for (int qb = 0; qb < 2; ++qb) {
+        const int blk = wq * 2 + qb;
+        // wave-uniform (the block index depends on the wave only): a scalar register
+        nbase[qb] = __uint_as_float((uint32_t)__builtin_amdgcn_readfirstlane(
+            (int)__float_as_uint(blk < nqb ? lse_s[blk * 32] : 0.f)));
 #pragma unroll
-        for (int r = 0; r < 16; ++r) nl[qb][r] *= inv_c2;
+        for (int r = 0; r < 16; ++r) nl[qb][r] = (nl[qb][r] - nbase[qb]) * inv_c2;
+      }
     }
   }
 
@@ -537,7 +553,7 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
           f32x16 cin = acc[p][qb];
           if (ks == 0) {
             cin = zero;
-            if (EMIT && TASK_MAX) {
+            if (EMIT && TASK_MAX && MF_EMIT_RECENTRE) {
 #pragma unroll
               for (int r = 0; r < 16; ++r) cin[r] = nl[qb][r];
             }
@@ -556,7 +572,7 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
             else if (i == 2) asm volatile("" : "+v"(carry.s[0]), "+v"(carry.s[1]), "+v"(carry.nmn[0]), "+v"(carry.nmn[1]));
             else asm volatile("" : "+v"(carry.s[0]), "+v"(carry.s[1]), "+v"(carry.e[0]), "+v"(carry.e[1]));
           } else {
-            emit_slice<TASK_MAX>(i, acc[p ^ 1][0], acc[p ^ 1][1], c2, nl, ev);
+            emit_slice<TASK_MAX>(i, acc[p ^ 1][0], acc[p ^ 1][1], c2, nl, nbase, ev);
           }
           __builtin_amdgcn_sched_barrier(0);
         }
@@ -591,7 +607,11 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
   __syncthreads();
   if (EMIT && ntiles > 0) epilogue(ntiles - 1, tail > 0 ? tail : MF_TILE);
   if (EMIT || track_all) break;
-  const int overflowed = !(srun[0] < 3.0e38f) || !(srun[1] < 3.0e38f);   // inf or NaN
+  // inf or NaN, tested on the bits: the library is compiled with the assumption that
+  // no NaN occurs, under which a floating-point comparison may drop the NaN case (a
+  // sum that overflowed to inf turns into NaN when a later tile rescales it by 0)
+  const int overflowed = (__float_as_uint(srun[0]) & 0x7f800000u) == 0x7f800000u ||
+                         (__float_as_uint(srun[1]) & 0x7f800000u) == 0x7f800000u;
   if (!__syncthreads_or(overflowed)) break;
   track_all = true;
   mrun[0] = mrun[1] = NEG_BIG;

@@ -40,8 +40,10 @@ constexpr int SEL_PER_BLOCK = SEL_THREADS * 8;   // fewest elements of a row per
 
 struct SelState {
   uint32_t prefix;       // bits of the threshold key fixed so far
-  uint32_t pad;
+  uint32_t bad;          // set when a histogram did not add up (see find_digit)
   uint64_t remaining;    // rank still to descend inside the prefix bucket (1-based)
+  uint64_t expect;       // candidates the next histogram pass must count: the pool, then
+                         // the population of the bucket chosen by the pass before
 };
 
 struct BudgetTable { int64_t b[KVC_MAX_BATCH]; };
@@ -55,10 +57,16 @@ __device__ __forceinline__ void digit_of(int pass, uint32_t key, uint32_t* digit
 
 // budget.b[] already excludes the floor entries
 __global__ void select_init(uint32_t* hist, int count, SelState* state, BudgetTable budget,
-                            int batch) {
+                            SeqTable seq, int rows, int floor_rank) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < count) hist[i] = 0;
-  if (i < batch) { state[i].prefix = 0; state[i].pad = 0; state[i].remaining = (uint64_t)budget.b[i]; }
+  if (i < seq.batch) {
+    const int n = seq.cu[i + 1] - seq.cu[i];
+    state[i].prefix = 0;
+    state[i].bad = 0;
+    state[i].remaining = (uint64_t)budget.b[i];
+    state[i].expect = (uint64_t)rows * (uint64_t)max(n - floor_rank, 0);   // entries that compete
+  }
 }
 
 __device__ __forceinline__ uint32_t load_agent(const uint32_t* p) {
@@ -66,13 +74,20 @@ __device__ __forceinline__ uint32_t load_agent(const uint32_t* p) {
 }
 
 // Ticket of a workgroup that has finished its part for sequence b: true for the
-// one that drew the last of `expected` tickets.  Workgroups hand data to the last
-// one through device-scope atomics only (histogram and count updates), which are
-// performed at the device's coherence point and are complete once the issuing
-// wave's memory counter has drained; so the release side is that wait, not a
-// device-scope fence (whose write-back of the whole L2 cost 150 us per launch
-// here, 2048 workgroups each paying it).  The last workgroup reads the totals
-// with device-scope atomic loads.
+// one that drew the last of `expected` tickets.
+//
+// INVARIANT: inside one kernel, workgroups hand data to the last one through
+// device-scope atomic read-modify-writes ONLY (histogram bins, row counts).  Those
+// are performed at the device's coherence point and are complete once the issuing
+// wave's vector-memory counter has drained; so the release side is that wait, not a
+// device-scope release fence (whose write-back of the whole L2 cost 150 us per
+// launch here, 2048 workgroups each paying it).  The last workgroup reads the totals
+// with device-scope atomic loads.  A plain store would NOT be visible to the last
+// workgroup this way: anything else a kernel produces (state[], lengths, offsets) is
+// written by the last workgroup itself and read by a later kernel.  This relies on
+// returned-less atomics counting in vmcnt and being performed in L2, which holds on
+// gfx950; find_digit checks that every histogram adds up to the population it must
+// cover, so a violation cannot pass silently (tau becomes NaN).
 // Tickets are drawn in two levels (groups of SEL_GROUP workgroups, then the groups
 // of a sequence), each counter on a cache line of its own: two thousand
 // workgroups drawing from one address took 30 us per launch.
@@ -83,7 +98,7 @@ constexpr int SEL_TICKET_WORDS = 32;   // one 128-byte line per counter
 __device__ __forceinline__ bool last_workgroup(uint32_t* tickets, int kernel_id, int batch, int b) {
   __shared__ uint32_t is_last;
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-  __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0): my atomics have been performed
+  wait_vmcnt<0>();                             // my atomics have been performed
   __syncthreads();
   if (threadIdx.x == 0) {
     const uint32_t nblocks = gridDim.x * gridDim.y;
@@ -132,6 +147,7 @@ __device__ __forceinline__ void find_digit(int pass, int b, const uint32_t* __re
                                            SelState* state) {
   const uint64_t want = state[b].remaining;    // uniform
   if (want == 0) return;                       // budget 0: nothing to find
+  const uint64_t expect = state[b].expect;     // uniform; read before anyone updates it
   const uint32_t* gh = hist + ((size_t)b * 3 + pass) * SEL_BINS;
   const int bins = pass == 2 ? 1024 : SEL_BINS;
   const int per = bins / SEL_THREADS;          // 8 or 4 bins per thread
@@ -145,14 +161,17 @@ __device__ __forceinline__ void find_digit(int pass, int b, const uint32_t* __re
   uint64_t total;
   const uint64_t incl = block_scan_incl(mine, &total);
   uint64_t run = incl - mine;
+  // every candidate of this pass must have been counted (see last_workgroup)
+  if (t == 0 && total != expect) state[b].bad = 1;
   // the thread whose range holds the rank; a rank past the pool ends in the last bin
   if (run < want && (want <= incl || t == SEL_THREADS - 1)) {
-    uint32_t digit = 0;
+    uint32_t digit = 0, population = 0;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       if (j < per) {
         const int bin = bins - 1 - (t * per + j);
         digit = (uint32_t)bin;
+        population = c[j];
         if (run + c[j] >= want) break;
         run += c[j];
       }
@@ -160,6 +179,7 @@ __device__ __forceinline__ void find_digit(int pass, int b, const uint32_t* __re
     const uint32_t shift = pass == 0 ? 21u : (pass == 1 ? 10u : 0u);
     state[b].prefix |= digit << shift;
     state[b].remaining = want - run;           // rank inside the chosen bucket
+    state[b].expect = population;              // what the next pass must count
   }
 }
 
@@ -238,7 +258,12 @@ __device__ __forceinline__ void finalize_sequence(int b, const SeqTable& seq, in
   const int n_b = seq.cu[b + 1] - seq.cu[b];
   const int64_t kept_first = floor_rank < n_b ? floor_rank : n_b;   // the floor entries
   const int t = threadIdx.x;
-  if (tau && t == 0) tau[b] = want > 0 ? ordered_to_float(state[b].prefix) : __builtin_inff();
+  if (tau && t == 0) {
+    // stored through the integer image: the library is compiled under the assumption
+    // that no NaN occurs, which a floating-point select of a NaN need not survive
+    const uint32_t bits = want > 0 ? __float_as_uint(ordered_to_float(state[b].prefix)) : 0x7f800000u;
+    reinterpret_cast<uint32_t*>(tau)[b] = state[b].bad ? 0x7fc00000u : bits;
+  }
   auto count_at = [&](size_t i) -> uint64_t { return AGENT ? load_agent(&counts[i]) : counts[i]; };
   uint64_t above_mine = 0;
   if (want > 0)
@@ -388,7 +413,7 @@ kvc_status launch_global_select(const Problem& pb, const float* I, const int64_t
   }
   const int total = int(pb.total);
 
-  KVC_LAUNCH("select_init", stream, select_init<<<(L.words + 255) / 256, 256, 0, stream>>>(hist, L.words, state, bt, pb.batch));
+  KVC_LAUNCH("select_init", stream, select_init<<<(L.words + 255) / 256, 256, 0, stream>>>(hist, L.words, state, bt, pb.seq, rows, floor_rank));
   if (pb.max_seqlen > 0) {
     const int per_block = select_per_block(pb);
     dim3 grid((unsigned)((pb.max_seqlen + per_block - 1) / per_block), rows, pb.batch);

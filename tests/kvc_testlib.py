@@ -45,6 +45,9 @@ class Workload:
         out = []
         kw.setdefault("causal_tail", bool(self.cfg.causal_tail))
         for b in range(self.cfg.batch):
+            if self.lens[b] == 0:          # the paper has no empty context; nothing to compute
+                out.append(None)
+                continue
             qs = [self.seq[b][l][0] for l in range(self.cfg.layers)]
             ks = [self.seq[b][l][1] for l in range(self.cfg.layers)]
             vs = [self.seq[b][l][2] for l in range(self.cfg.layers)]
@@ -121,6 +124,11 @@ def check_end_to_end(w: Workload, got: dict, ref: list, eps: float = EPS):
     for b in range(c.batch):
         lo, hi = int(w.cu[b]), int(w.cu[b + 1])
         n = hi - lo
+        if n == 0:                         # empty sequence: budget 0, every length 0
+            assert w.budgets[b] == 0 and (got["lengths"][b] == 0).all()
+            for l in range(c.layers):
+                assert off[b * c.layers + l + 1] == off[b * c.layers + l]
+            continue
         r = ref[b]
         B = w.budgets[b]
         S_g = got["S"][:, :, lo:hi]

@@ -171,6 +171,8 @@ def test_handworked_composite_fixture():
     np.testing.assert_array_equal(ss, g["S_sorted"])
     i_all = np.stack([orc.composite(ss[l]) for l in range(2)])
     np.testing.assert_array_equal(i_all, g["I"])
+    i_max = np.stack([orc.composite(ss[l], MAX) for l in range(2)])
+    np.testing.assert_array_equal(i_max, g["I_max"])          # head aggregator = max-pooling
     for case in g["select"]:
         lengths, tau = orc.global_select(i_all, case["budget"])
         assert lengths.tolist() == case["lengths"], case
