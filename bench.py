@@ -415,7 +415,13 @@ def main():
     if dom.startswith("score_mfma"):
         c, ms = per_step[dom]
         layers_per_launch = cfg.layers / c
-        flops_per_launch = 2.0 * cfg.hq * cfg.window * cfg.head_dim * total * layers_per_launch
+        # query rows the launch covers: all Hq*M, or, when the small last row chunk of every
+        # KV head runs as a launch of its own (",rem"), the full 256-row chunks / that chunk
+        rows_head = cfg.group * cfg.window
+        rows = cfg.hq * cfg.window
+        if any(k.endswith(",rem") for k in per_step):
+            rows = cfg.hkv * (rows_head % 256 if dom.endswith(",rem") else rows_head // 256 * 256)
+        flops_per_launch = 2.0 * rows * cfg.head_dim * total * layers_per_launch
         avg_s = ms / c * 1e-3
         achieved = flops_per_launch / avg_s / 1e12
         shape = {"hq": cfg.hq, "hkv": cfg.hkv, "head_dim": cfg.head_dim, "window": cfg.window,

@@ -497,18 +497,30 @@ kvc_status launch_score(const Problem& pb, const void* const* q, const void* con
     for (int b = 0; b < pb.batch; ++b)
       flat_chunks += (pb.seq.cu[b + 1] - pb.seq.cu[b] + chunk - 1) / chunk;
     if ((chunk & (chunk - 1)) != 0) { set_error("internal: chunk length %d not a power of two", chunk); return KVC_ERR_INVALID_ARG; }
-    dim3 grid(flat_chunks > 0 ? flat_chunks : 1, pb.hkv * L.row_chunks, pb.layers);
-    const int nqb0 = (pb.group * pb.window < MF_RCHUNK ? pb.group * pb.window : MF_RCHUNK) / 32;
+    const int rows_head = pb.group * pb.window;                  // query rows per KV head
+    const int nqb0 = (rows_head < MF_RCHUNK ? rows_head : MF_RCHUNK) / 32;
     const int rows_all = L.rows_layer * pb.layers;
-#define KVC_SCORE_MFMA(NAME, EMIT, TMAX, WQ, PM, PS, LSE, OUT)                                   \
-  KVC_LAUNCH(NAME, stream, score_mfma<EMIT, TMAX, WQ><<<grid, MF_THREADS, 0, stream>>>(           \
+    // The last row chunk of a head may hold few rows (G = 5 at M = 64: 256 + 64).  With
+    // four waves along the rows it would cost a full 256-row pass, so when it has at most
+    // four 32-row blocks it gets a launch of its own in which the waves split the keys.
+    const int rem_blocks = (rows_head % MF_RCHUNK) / 32;         // 0: every chunk is full
+    const bool split = L.row_chunks > 1 && rem_blocks > 0 && rem_blocks <= 4;
+    const int main_chunks = split ? L.row_chunks - 1 : L.row_chunks;
+    const unsigned gx = flat_chunks > 0 ? flat_chunks : 1;
+#define KVC_SCORE_MFMA(NAME, EMIT, TMAX, WQ, RCS, RC0, PM, PS, LSE, OUT)                         \
+  KVC_LAUNCH(NAME, stream, score_mfma<EMIT, TMAX, WQ><<<dim3(gx, pb.hkv * (RCS), pb.layers), MF_THREADS, 0, stream>>>( \
       qt, kt, pb.batch, out_stride, pb.seq, pb.hq, pb.group, pb.window, total, c2, chunk,        \
-      L.row_chunks, PM, PS, LSE, group_max, pb.causal_tail, OUT))
-#define KVC_SCORE_MFMA_WQ(NAME, EMIT, TMAX, PM, PS, LSE, OUT)                     \
-  do {                                                                            \
-    if (nqb0 <= 2) { KVC_SCORE_MFMA(NAME, EMIT, TMAX, 1, PM, PS, LSE, OUT); }       \
-    else if (nqb0 <= 4) { KVC_SCORE_MFMA(NAME, EMIT, TMAX, 2, PM, PS, LSE, OUT); }  \
-    else { KVC_SCORE_MFMA(NAME, EMIT, TMAX, 4, PM, PS, LSE, OUT); }                 \
+      RCS, RC0, PM, PS, LSE, group_max, pb.causal_tail, OUT))
+#define KVC_SCORE_MFMA_BLOCKS(NAME, EMIT, TMAX, BLOCKS, RCS, RC0, PM, PS, LSE, OUT)                  \
+  do {                                                                                             \
+    if ((BLOCKS) <= 2) { KVC_SCORE_MFMA(NAME, EMIT, TMAX, 1, RCS, RC0, PM, PS, LSE, OUT); }          \
+    else if ((BLOCKS) <= 4) { KVC_SCORE_MFMA(NAME, EMIT, TMAX, 2, RCS, RC0, PM, PS, LSE, OUT); }     \
+    else { KVC_SCORE_MFMA(NAME, EMIT, TMAX, 4, RCS, RC0, PM, PS, LSE, OUT); }                        \
+  } while (0)
+#define KVC_SCORE_MFMA_WQ(NAME, EMIT, TMAX, PM, PS, LSE, OUT)                                                   \
+  do {                                                                                                          \
+    KVC_SCORE_MFMA_BLOCKS(NAME, EMIT, TMAX, nqb0, main_chunks, 0, PM, PS, LSE, OUT);                            \
+    if (split) KVC_SCORE_MFMA_BLOCKS(NAME ",rem", EMIT, TMAX, rem_blocks, 1, main_chunks, PM, PS, LSE, OUT);    \
   } while (0)
     if (chunks > 0) {
       KVC_SCORE_MFMA_WQ("score_mfma<stats>", false, true, part_m, part_s, nullptr, nullptr);
@@ -526,6 +538,7 @@ kvc_status launch_score(const Problem& pb, const void* const* q, const void* con
       }
     }
 #undef KVC_SCORE_MFMA_WQ
+#undef KVC_SCORE_MFMA_BLOCKS
 #undef KVC_SCORE_MFMA
     if (vnorm && pb.layers > 0 && total > 0) {   // value norms and finish of all layers, one launch each
       PtrTable vt{};

@@ -188,6 +188,9 @@ __device__ __forceinline__ void lds_dma16_s(const void* sbase, uint32_t voff, ui
 
 // grid: ((sequence, chunk) pairs, Hkv * row_chunks, Lyr), 256 threads.  WQ = waves along the query
 // rows (each owns 2 blocks of 32 rows); the other 4/WQ waves split the key tiles.
+// A launch covers the row chunks [rc_offset, rc_offset + row_chunks) of every KV head
+// (the last, partly filled row chunk of a head may get a launch of its own with fewer
+// waves along the rows).
 //
 // Schedule of one workgroup over its macro tiles (two K buffers, tile t in
 // buffer t&1), for an even number NT of 32-key tiles per wave:
@@ -207,7 +210,7 @@ template <bool EMIT, bool TASK_MAX, int WQ>
 __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
     PtrTable q_tab, PtrTable k_tab, int batch, size_t out_layer_stride, SeqTable seq,
     int hq, int group, int window, int total, float c2, int chunk_keys, int row_chunks,
-    float* __restrict__ part_m, float* __restrict__ part_s, const float* __restrict__ lse2,
+    int rc_offset, float* __restrict__ part_m, float* __restrict__ part_s, const float* __restrict__ lse2,
     int group_max, int causal, float* __restrict__ out) {
   constexpr int WK = 4 / WQ;        // waves along the keys
   constexpr int NT = 4 / WK;        // 32-key tiles per wave per macro tile
@@ -242,7 +245,7 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
   if (key_begin >= n) return;
   const int key_end = min(n, key_begin + chunk_keys);
   const int hkv = gridDim.y / row_chunks;
-  const int h = blockIdx.y / row_chunks, rc = blockIdx.y - h * row_chunks;
+  const int h = blockIdx.y / row_chunks, rc = blockIdx.y - h * row_chunks + rc_offset;
   const int R = group * window;
   const int row0 = rc * MF_RCHUNK;
   const int nqb = (min(R, row0 + MF_RCHUNK) - row0) / 32;   // q blocks in this row chunk
