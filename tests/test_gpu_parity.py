@@ -125,7 +125,7 @@ def _rank_inputs(kind, lyr, hkv, lens, seed):
 
 @pytest.mark.parametrize("kind", ["scores", "ties", "signed", "constant"])
 @pytest.mark.parametrize("lens", [[1], [63], [2047], [2048, 2049], [4096], [4097], [8192, 8193],
-                                  [9000, 1, 300], [20000]])
+                                  [9000, 1, 300], [20000], [16384, 16385], [40000]])
 def test_head_rank_bit_exact(kind, lens):
     _say(f"rank {kind} lens={lens}")
     lyr, hkv = 2, 3
