@@ -182,12 +182,17 @@ __global__ __launch_bounds__(256) void score_emit_generic(
 // ---------------------------------------------------------------------------
 constexpr int MERGE_ROWS = 16;
 
+// (Both merge kernels also clear the two counters of the emit pass's defer lists, which
+// sit DEFER_COUNTER_STRIDE words apart: the merge always runs between stats and emit.)
+constexpr int DEFER_COUNTER_STRIDE = 64;
 __global__ __launch_bounds__(256) void score_merge(SeqTable seq, int rows_per_seq, int layers,
                                                    int chunk_keys,
                                                    const float* __restrict__ part_m,
                                                    const float* __restrict__ part_s,
-                                                   float* __restrict__ lse2) {
+                                                   float* __restrict__ lse2,
+                                                   uint32_t* __restrict__ defer_counters) {
   __shared__ float sm[16][MERGE_ROWS], ss[16][MERGE_ROWS];
+  if (defer_counters && blockIdx.x == 0 && threadIdx.x < 2) defer_counters[threadIdx.x * DEFER_COUNTER_STRIDE] = 0;
   const int r = threadIdx.x & (MERGE_ROWS - 1), cg = threadIdx.x >> 4;
   // rows of every layer of the launch: row = (layer * batch + sequence) * rows_per_seq + ...
   const int rows = rows_per_seq * seq.batch * layers;
@@ -225,7 +230,9 @@ __global__ __launch_bounds__(256) void score_merge_few(SeqTable seq, int rows_pe
                                                        int chunk_keys,
                                                        const float* __restrict__ part_m,
                                                        const float* __restrict__ part_s,
-                                                       float* __restrict__ lse2) {
+                                                       float* __restrict__ lse2,
+                                                       uint32_t* __restrict__ defer_counters) {
+  if (defer_counters && blockIdx.x == 0 && threadIdx.x < 2) defer_counters[threadIdx.x * DEFER_COUNTER_STRIDE] = 0;
   const int rows = rows_per_seq * seq.batch * layers;
   const int row = blockIdx.x * 256 + threadIdx.x;
   if (row >= rows) return;
@@ -422,9 +429,11 @@ inline int mfma_chunk(const Problem& pb, int row_chunks) {
   return wgs >= 2048 ? MF_CHUNK_BIG : MF_CHUNK;
 }
 constexpr int MIN_CHUNK = 256;   // workspace is sized for the smallest chunk in use
+constexpr int MF_LISTED_BLOCKS = 512;   // workgroups of the list-driven exact emit launch (two per compute unit)
 
 struct ScoreLayout {
-  size_t off_m, off_s, off_lse, off_part, off_vnorm, total, part_layer;
+  size_t off_m, off_s, off_lse, off_part, off_vnorm, off_defer, total, part_layer;
+  size_t defer_capacity;   // entries per defer list: an upper bound of the workgroups of one emit launch
   int max_chunks, rows_layer, row_chunks, layers_held;
 };
 
@@ -451,6 +460,14 @@ ScoreLayout score_layout(const Problem& pb) {
   if (L.row_chunks > 1 || pb.hkv > 8) cur += align_up(L.part_layer * L.layers_held * 4);
   L.off_vnorm = cur;
   if (pb.value_norm) cur += align_up(size_t(L.layers_held) * pb.hkv * size_t(pb.total) * 4);
+  // defer lists of the emit pass (matrix-core path): two counters, then two lists of block
+  // indices; a launch has at most (total/chunk + batch) x hkv x row_chunks x layers workgroups
+  L.off_defer = cur;
+  L.defer_capacity = 0;
+  if (mfma) {
+    L.defer_capacity = (size_t(pb.total) / MF_CHUNK + size_t(pb.batch)) * pb.hkv * L.row_chunks * pb.layers;
+    cur += align_up(2 * DEFER_COUNTER_STRIDE * 4) + align_up(2 * L.defer_capacity * 8);
+  }
   L.total = cur;
   return L;
 }
@@ -507,10 +524,26 @@ kvc_status launch_score(const Problem& pb, const void* const* q, const void* con
     const bool split = L.row_chunks > 1 && rem_blocks > 0 && rem_blocks <= 4;
     const int main_chunks = split ? L.row_chunks - 1 : L.row_chunks;
     const unsigned gx = flat_chunks > 0 ? flat_chunks : 1;
+    // Max-pooling emit pass: a workgroup whose log-sum-exps are too far apart for the cheap
+    // form puts itself on a list (one for the main launch, one for the remainder launch)
+    // and a small list-driven launch right behind redoes the listed ones in the exact form.
+    uint32_t* defer_counters = reinterpret_cast<uint32_t*>(w + L.off_defer);
+    uint64_t* defer_entries = reinterpret_cast<uint64_t*>(w + L.off_defer + align_up(2 * DEFER_COUNTER_STRIDE * 4));
+    const uint32_t defer_cap = (uint32_t)(L.defer_capacity < 0xffffffffu ? L.defer_capacity : 0xffffffffu);
+    const DeferList defer_main{defer_counters, defer_entries, defer_cap};
+    const DeferList defer_rem{defer_counters + DEFER_COUNTER_STRIDE, defer_entries + L.defer_capacity, defer_cap};
+    const DeferList defer_none{nullptr, nullptr, 0};
 #define KVC_SCORE_MFMA(NAME, EMIT, TMAX, WQ, RCS, RC0, PM, PS, LSE, OUT)                         \
-  KVC_LAUNCH(NAME, stream, score_mfma<EMIT, TMAX, WQ><<<dim3(gx, pb.hkv * (RCS), pb.layers), MF_THREADS, 0, stream>>>( \
-      qt, kt, pb.batch, out_stride, pb.seq, pb.hq, pb.group, pb.window, total, c2, chunk,        \
-      RCS, RC0, PM, PS, LSE, group_max, pb.causal_tail, OUT))
+  do {                                                                                           \
+    const DeferList dl_ = (EMIT && TMAX) ? ((RC0) == 0 ? defer_main : defer_rem) : defer_none;   \
+    KVC_LAUNCH(NAME, stream, score_mfma<EMIT, TMAX, WQ><<<dim3(gx, pb.hkv * (RCS), pb.layers), MF_THREADS, 0, stream>>>( \
+        qt, kt, pb.batch, out_stride, pb.seq, pb.hq, pb.group, pb.window, total, c2, chunk,      \
+        RCS, RC0, PM, PS, LSE, group_max, pb.causal_tail, OUT, dl_));                            \
+    if (EMIT && TMAX)                                                                            \
+      KVC_LAUNCH(NAME ",exact", stream, score_mfma_listed<WQ><<<MF_LISTED_BLOCKS, MF_THREADS, 0, stream>>>( \
+          qt, kt, pb.batch, out_stride, pb.seq, pb.hq, pb.group, pb.window, total, c2, chunk,    \
+          RCS, RC0, LSE, group_max, pb.causal_tail, OUT, dl_, (int)gx, pb.hkv * (RCS), pb.layers)); \
+  } while (0)
 #define KVC_SCORE_MFMA_BLOCKS(NAME, EMIT, TMAX, BLOCKS, RCS, RC0, PM, PS, LSE, OUT)                  \
   do {                                                                                             \
     if ((BLOCKS) <= 2) { KVC_SCORE_MFMA(NAME, EMIT, TMAX, 1, RCS, RC0, PM, PS, LSE, OUT); }          \
@@ -526,10 +559,10 @@ kvc_status launch_score(const Problem& pb, const void* const* q, const void* con
       KVC_SCORE_MFMA_WQ("score_mfma<stats>", false, true, part_m, part_s, nullptr, nullptr);
       if (chunks <= 4) {
         KVC_LAUNCH("score_merge", stream, score_merge_few<<<(rows_all + 255) / 256, 256, 0, stream>>>(
-            pb.seq, rows_per_seq, pb.layers, chunk, part_m, part_s, lse2));
+            pb.seq, rows_per_seq, pb.layers, chunk, part_m, part_s, lse2, defer_counters));
       } else {
         KVC_LAUNCH("score_merge", stream, score_merge<<<(rows_all + MERGE_ROWS - 1) / MERGE_ROWS, 256, 0, stream>>>(
-            pb.seq, rows_per_seq, pb.layers, chunk, part_m, part_s, lse2));
+            pb.seq, rows_per_seq, pb.layers, chunk, part_m, part_s, lse2, defer_counters));
       }
       if (task_max) {
         KVC_SCORE_MFMA_WQ("score_mfma<emit>", true, true, nullptr, nullptr, lse2, part_all);
@@ -588,7 +621,7 @@ kvc_status launch_score(const Problem& pb, const void* const* q, const void* con
             ql, kl, pb.seq, pb.hq, pb.group, pb.window, pb.d, total, c2, chunk, L.max_chunks,
             pb.causal_tail, part_m, part_s));
         KVC_LAUNCH("score_merge", stream, score_merge<<<(L.rows_layer + MERGE_ROWS - 1) / MERGE_ROWS, 256, 0, stream>>>(
-            pb.seq, rows_per_seq, 1, chunk, part_m, part_s, lse2));
+            pb.seq, rows_per_seq, 1, chunk, part_m, part_s, lse2, nullptr));
         KVC_LAUNCH("score_emit_generic", stream, score_emit_generic<uint16_t><<<ge, 256, lds_e, stream>>>(
             ql, kl, pb.seq, pb.hq, pb.group, pb.window, pb.d, total, c2, chunk, lse2, task_max,
             group_max, pb.causal_tail, part));
@@ -599,7 +632,7 @@ kvc_status launch_score(const Problem& pb, const void* const* q, const void* con
             ql, kl, pb.seq, pb.hq, pb.group, pb.window, pb.d, total, c2, chunk, L.max_chunks,
             pb.causal_tail, part_m, part_s));
         KVC_LAUNCH("score_merge", stream, score_merge<<<(L.rows_layer + MERGE_ROWS - 1) / MERGE_ROWS, 256, 0, stream>>>(
-            pb.seq, rows_per_seq, 1, chunk, part_m, part_s, lse2));
+            pb.seq, rows_per_seq, 1, chunk, part_m, part_s, lse2, nullptr));
         KVC_LAUNCH("score_emit_generic", stream, score_emit_generic<float><<<ge, 256, lds_e, stream>>>(
             ql, kl, pb.seq, pb.hq, pb.group, pb.window, pb.d, total, c2, chunk, lse2, task_max,
             group_max, pb.causal_tail, part));

@@ -133,40 +133,39 @@ __device__ __forceinline__ void stats_slice(int i, const f32x16& x0, const f32x1
 // max of t, or sum of 2^t, with t = logit*c2 - lse2 (nl holds -lse2 of the lane's 16
 // rows).  Result in both half-waves.
 //
-// MF_EMIT_RECENTRE (TASK_MAX only) is the cheaper form: the accumulators start from
+// RECENTRE (TASK_MAX only) is the cheaper form: the accumulators start from
 // -(lse2[row] - lse2[first row of the block])/c2 (nl holds that) instead of zero, so
 // they are (t + lse2[first row])/c2; the maximum commutes with the positive factor c2
 // and the common shift, which are applied once at the end (one FMA with base =
 // -lse2[first row]) instead of once per element.  It costs accuracy in proportion to
-// the start value: nothing while the rows of a block have similar log-sum-exps, up to
-// 2e-4 relative when they lie hundreds of units apart.  Off: every element gets its
-// own FMA and the accuracy does not depend on the data.
-#ifndef KVC_EMIT_RECENTRE
-#define KVC_EMIT_RECENTRE 0
-#endif
-constexpr bool MF_EMIT_RECENTRE = KVC_EMIT_RECENTRE != 0;
-template <bool TASK_MAX>
+// the start value: nothing while the rows of a block have similar log-sum-exps (those
+// of one query head do), up to 2e-4 relative when they lie hundreds of units apart.
+// So a workgroup uses it only if every block of its row chunk lies within
+// EMIT_SPREAD_LIMIT of its first row; otherwise the workgroup is redone in the exact
+// form (every element gets its own FMA; accuracy independent of the data).
+constexpr float EMIT_SPREAD_LIMIT = 64.f;   // log2 units: keeps the start value's rounding below 1e-5 relative
+template <bool TASK_MAX, bool RECENTRE>
 __device__ __forceinline__ float emit_fold(const f32x16& acc, float c2, const float (&nl)[16],
                                            float base) {
   float v = TASK_MAX ? NEG_BIG : 0.f;
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
-    if (TASK_MAX) v = fmaxf(v, MF_EMIT_RECENTRE ? acc[r] : fmaf(acc[r], c2, nl[r]));
+    if (TASK_MAX) v = fmaxf(v, RECENTRE ? acc[r] : fmaf(acc[r], c2, nl[r]));
     else v += fast_exp2(fmaf(acc[r], c2, nl[r]));
   }
   v = cross_half<TASK_MAX>(v);
-  return (TASK_MAX && MF_EMIT_RECENTRE) ? fmaf(v, c2, base) : v;
+  return (TASK_MAX && RECENTRE) ? fmaf(v, c2, base) : v;
 }
 // The same for two tiles in 16 slices: slice i handles elements 2(i%8), 2(i%8)+1 of
 // tile i/8; the cross-half combine of a tile follows its last slice.
-template <bool TASK_MAX>
+template <bool TASK_MAX, bool RECENTRE>
 __device__ __forceinline__ void emit_slice(int i, const f32x16& x0, const f32x16& x1, float c2,
                                            const float (&nl)[2][16], const float (&base)[2],
                                            float (&v)[2]) {
   const int b = i >> 3, r = 2 * (i & 7);
   const f32x16& x = b ? x1 : x0;
   if ((i & 7) == 0) v[b] = TASK_MAX ? NEG_BIG : 0.f;
-  if (TASK_MAX && MF_EMIT_RECENTRE) {
+  if (TASK_MAX && RECENTRE) {
     v[b] = fmaxf(v[b], fmaxf(x[r], x[r + 1]));
   } else if (TASK_MAX) {
     v[b] = fmaxf(v[b], fmaxf(fmaf(x[r], c2, nl[b][r]), fmaf(x[r + 1], c2, nl[b][r + 1])));
@@ -176,7 +175,7 @@ __device__ __forceinline__ void emit_slice(int i, const f32x16& x0, const f32x16
   }
   if ((i & 7) == 7) {
     v[b] = cross_half<TASK_MAX>(v[b]);
-    if (TASK_MAX && MF_EMIT_RECENTRE) v[b] = fmaf(v[b], c2, base[b]);
+    if (TASK_MAX && RECENTRE) v[b] = fmaf(v[b], c2, base[b]);
   }
 }
 
@@ -206,12 +205,26 @@ __device__ __forceinline__ void lds_dma16_s(const void* sbase, uint32_t voff, ui
 // sees keys at positions <= that only.  Tiles that lie wholly below position
 // n - window + 1 are visible to every row and go through the pipeline; the few
 // tiles above it are processed one key tile at a time with the mask applied.
-template <bool EMIT, bool TASK_MAX, int WQ>
-__global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
-    PtrTable q_tab, PtrTable k_tab, int batch, size_t out_layer_stride, SeqTable seq,
-    int hq, int group, int window, int total, float c2, int chunk_keys, int row_chunks,
-    int rc_offset, float* __restrict__ part_m, float* __restrict__ part_s, const float* __restrict__ lse2,
-    int group_max, int causal, float* __restrict__ out) {
+//
+// MODE (EMIT with TASK_MAX only; 0 otherwise): 1 = the re-centred form of emit_fold,
+// with the workgroup checking its log-sum-exps first and, when they are too far apart,
+// putting its block index (bx, by, bz) on the `defer` list instead of working; 2 = the
+// exact form, which the list-driven kernel below runs for the listed workgroups.
+// (bx, by, bz) and (gy, gz) stand for blockIdx and gridDim.y/z of the grid launch.
+struct DeferList {
+  uint32_t* count;        // device: number of entries appended so far
+  uint64_t* entries;      // device: bx | by << 32 | bz << 56
+  uint32_t capacity;
+};
+template <bool EMIT, bool TASK_MAX, int WQ, int MODE>
+__device__ __forceinline__ void score_mfma_body(
+    const PtrTable& q_tab, const PtrTable& k_tab, int batch, size_t out_layer_stride,
+    const SeqTable& seq, int hq, int group, int window, int total, float c2, int chunk_keys,
+    int row_chunks, int rc_offset, float* __restrict__ part_m, float* __restrict__ part_s,
+    const float* __restrict__ lse2, int group_max, int causal, float* __restrict__ out,
+    const DeferList& defer, const int bx, const int by, const int bz, const int gy, const int gz) {
+  static_assert(MODE == 0 || (EMIT && TASK_MAX), "modes 1 and 2 are forms of the max-pooling emit pass");
+  constexpr bool RECENTRE = MODE == 1;
   constexpr int WK = 4 / WQ;        // waves along the keys
   constexpr int NT = 4 / WK;        // 32-key tiles per wave per macro tile
   constexpr bool PIPE = NT % 2 == 0;
@@ -228,9 +241,9 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
   // the hardware deals round-robin to the eight XCDs, carry equal work whatever the
   // mix of sequence lengths (a chunk-major grid gave XCD j the j-th chunk of every
   // sequence: twice the time on a batch of 5k..29k-token sequences).
-  const int layer = blockIdx.z;
+  const int layer = bz;
   const int chunk_shift = __builtin_ctz(chunk_keys);   // chunk_keys is a power of two (host-checked)
-  int b = 0, chunk = blockIdx.x;
+  int b = 0, chunk = bx;
   for (; b < batch - 1; ++b) {
     const int nc = (seq.cu[b + 1] - seq.cu[b] + chunk_keys - 1) >> chunk_shift;
     if (chunk < nc) break;
@@ -244,8 +257,8 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
   const int key_begin = chunk * chunk_keys;
   if (key_begin >= n) return;
   const int key_end = min(n, key_begin + chunk_keys);
-  const int hkv = gridDim.y / row_chunks;
-  const int h = blockIdx.y / row_chunks, rc = blockIdx.y - h * row_chunks + rc_offset;
+  const int hkv = gy / row_chunks;
+  const int h = by / row_chunks, rc = by - h * row_chunks + rc_offset;
   const int R = group * window;
   const int row0 = rc * MF_RCHUNK;
   const int nqb = (min(R, row0 + MF_RCHUNK) - row0) / 32;   // q blocks in this row chunk
@@ -312,7 +325,7 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
   if (EMIT && (int)threadIdx.x < nqb * 32)
     my_nl = -lse2[((size_t)zid * hq + h * group) * window + row0 + threadIdx.x];
   float nl[2][16];   // EMIT: minus lse2 of the lane's accumulator rows, filled after the first barrier
-  float nbase[2] = {0.f, 0.f};   // MF_EMIT_RECENTRE: minus lse2 of the first row of each q block
+  float nbase[2] = {0.f, 0.f};   // RECENTRE: minus lse2 of the first row of each q block
 
   float mrun[2] = {NEG_BIG, NEG_BIG}, srun[2] = {0.f, 0.f};   // STATS, in log2 units
   const int bpg = window / 32;                                 // q blocks per query head
@@ -342,8 +355,8 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
   auto mfma_tile = [&](f32x16 (&a)[2], const uint4 (&kf)[8]) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      a[0][r] = (EMIT && TASK_MAX && MF_EMIT_RECENTRE) ? nl[0][r] : 0.f;
-      a[1][r] = (EMIT && TASK_MAX && MF_EMIT_RECENTRE) ? nl[1][r] : 0.f;
+      a[0][r] = (EMIT && TASK_MAX && RECENTRE) ? nl[0][r] : 0.f;
+      a[1][r] = (EMIT && TASK_MAX && RECENTRE) ? nl[1][r] : 0.f;
     }
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
@@ -379,8 +392,8 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
   };
   auto emit_store = [&](const f32x16 (&a)[2], int buf, int kt) {
     float v[2];
-    v[0] = emit_fold<TASK_MAX>(a[0], c2, nl[0], nbase[0]);
-    v[1] = emit_fold<TASK_MAX>(a[1], c2, nl[1], nbase[1]);
+    v[0] = emit_fold<TASK_MAX, RECENTRE>(a[0], c2, nl[0], nbase[0]);
+    v[1] = emit_fold<TASK_MAX, RECENTRE>(a[1], c2, nl[1], nbase[1]);
     red_store(v, buf, kt);
   };
   // EMIT: threads 0..127 turn red[buf] into the group value of one key each
@@ -486,6 +499,21 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
   int issued = ntiles > 1 ? 1 : 0;            // highest tile requested so far
   __syncthreads();
 
+  // MODE 1: the re-centred form needs the rows of each block close to its first row;
+  // a workgroup that finds them too far apart hands itself to the exact kernel
+  if (MODE == 1) {
+    const bool far = (int)threadIdx.x < nqb * 32 &&
+                     fabsf(my_nl - lse_s[threadIdx.x & ~31]) > EMIT_SPREAD_LIMIT;
+    if (__syncthreads_or(far)) {
+      wait_vmcnt<0>();   // tile loads in flight must land before this workgroup's LDS is given back
+      if (threadIdx.x == 0) {
+        const uint32_t slot = atomicAdd(defer.count, 1u);
+        if (slot < defer.capacity)
+          defer.entries[slot] = (uint64_t)(uint32_t)bx | ((uint64_t)(uint32_t)by << 32) | ((uint64_t)(uint32_t)bz << 56);
+      }
+      return;
+    }
+  }
   // EMIT: minus lse2 of the 16 accumulator rows of each q block held by this lane
   // (register r is row 8 (r/4) + 4 half + r%4: four consecutive rows per 16 bytes)
   if (EMIT) {
@@ -500,7 +528,7 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
         nl[qb][4 * i + 0] = v.x; nl[qb][4 * i + 1] = v.y; nl[qb][4 * i + 2] = v.z; nl[qb][4 * i + 3] = v.w;
       }
     }
-    if (TASK_MAX && MF_EMIT_RECENTRE) {   // accumulators start from -(lse2 - lse2[first row])/c2
+    if (TASK_MAX && RECENTRE) {   // accumulators start from -(lse2 - lse2[first row])/c2
       const float inv_c2 = 1.f / c2;
 #pragma unroll
       for (int qb = 0; qb < 2; ++qb) {
@@ -522,7 +550,7 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
     load_frags(kf, kbuf[0] + wk * 8192);
     // Two workgroups share a CU and the hardware favours the older one; alternating
     // the wave priority per tile keeps them advancing at the same pace.
-    const int prio_phase = (blockIdx.y * 2 >= gridDim.y) ? 1 : 0;
+    const int prio_phase = (by * 2 >= gy) ? 1 : 0;
     for (int it = 0; it < npipe; ++it) {
       if ((it + prio_phase) & 1) __builtin_amdgcn_s_setprio(1);
       else __builtin_amdgcn_s_setprio(0);
@@ -556,7 +584,7 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
           f32x16 cin = acc[p][qb];
           if (ks == 0) {
             cin = zero;
-            if (EMIT && TASK_MAX && MF_EMIT_RECENTRE) {
+            if (EMIT && TASK_MAX && RECENTRE) {
 #pragma unroll
               for (int r = 0; r < 16; ++r) cin[r] = nl[qb][r];
             }
@@ -575,7 +603,7 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
             else if (i == 2) asm volatile("" : "+v"(carry.s[0]), "+v"(carry.s[1]), "+v"(carry.nmn[0]), "+v"(carry.nmn[1]));
             else asm volatile("" : "+v"(carry.s[0]), "+v"(carry.s[1]), "+v"(carry.e[0]), "+v"(carry.e[1]));
           } else {
-            emit_slice<TASK_MAX>(i, acc[p ^ 1][0], acc[p ^ 1][1], c2, nl, nbase, ev);
+            emit_slice<TASK_MAX, RECENTRE>(i, acc[p ^ 1][0], acc[p ^ 1][1], c2, nl, nbase, ev);
           }
           __builtin_amdgcn_sched_barrier(0);
         }
@@ -651,10 +679,44 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
       // row index over all layers and sequences of the launch
       const size_t qrow = ((size_t)zid * hq + h * group) * window + r;
       // partial statistics are stored chunk-major so the merge reads coalesced
-      const size_t rows_all = (size_t)gridDim.z * batch * hq * window;
+      const size_t rows_all = (size_t)gz * batch * hq * window;
       part_m[(size_t)chunk * rows_all + qrow] = mm;
       part_s[(size_t)chunk * rows_all + qrow] = ss;
     }
+  }
+}
+
+// The grid-indexed kernel: workgroup (blockIdx) = ((sequence, chunk) pair, KV head x row chunk, layer).
+template <bool EMIT, bool TASK_MAX, int WQ>
+__global__ __launch_bounds__(MF_THREADS, 2) void score_mfma(
+    PtrTable q_tab, PtrTable k_tab, int batch, size_t out_layer_stride, SeqTable seq,
+    int hq, int group, int window, int total, float c2, int chunk_keys, int row_chunks,
+    int rc_offset, float* __restrict__ part_m, float* __restrict__ part_s, const float* __restrict__ lse2,
+    int group_max, int causal, float* __restrict__ out, DeferList defer) {
+  score_mfma_body<EMIT, TASK_MAX, WQ, (EMIT && TASK_MAX) ? 1 : 0>(
+      q_tab, k_tab, batch, out_layer_stride, seq, hq, group, window, total, c2, chunk_keys,
+      row_chunks, rc_offset, part_m, part_s, lse2, group_max, causal, out, defer,
+      (int)blockIdx.x, (int)blockIdx.y, (int)blockIdx.z, (int)gridDim.y, (int)gridDim.z);
+}
+
+// The list-driven kernel: redoes, in the exact form, the workgroups of the max-pooling
+// emit launch with grid (gx, gy, gz) that put themselves on the list.  Workgroup i takes
+// entries i, i + gridDim.x, ...; an empty list costs one load per workgroup.
+template <int WQ>
+__global__ __launch_bounds__(MF_THREADS, 2) void score_mfma_listed(
+    PtrTable q_tab, PtrTable k_tab, int batch, size_t out_layer_stride, SeqTable seq,
+    int hq, int group, int window, int total, float c2, int chunk_keys, int row_chunks,
+    int rc_offset, const float* __restrict__ lse2, int group_max, int causal,
+    float* __restrict__ out, DeferList defer, int gx, int gy, int gz) {
+  const uint32_t listed = min(*defer.count, defer.capacity);     // appended by the launch before this one
+  for (uint32_t i = blockIdx.x; i < listed; i += gridDim.x) {
+    const uint64_t e = defer.entries[i];
+    const int bx = (int)(uint32_t)(e & 0xffffffffu), by = (int)((e >> 32) & 0xffffffu), bz = (int)(e >> 56);
+    if (bx < gx && by < gy && bz < gz)     // entries are this library's own block indices; checked all the same
+      score_mfma_body<true, true, WQ, 2>(q_tab, k_tab, batch, out_layer_stride, seq, hq, group, window,
+                                         total, c2, chunk_keys, row_chunks, rc_offset, nullptr, nullptr,
+                                         lse2, group_max, causal, out, defer, bx, by, bz, gy, gz);
+    __syncthreads();   // the next entry reuses the LDS
   }
 }
 
