@@ -170,3 +170,28 @@ def test_static_select_rejects_what_its_buffer_cannot_hold():
     # and the argument checks of kvc_global_select apply unchanged
     expect(1, kv.kvc_global_select_static, P(), FAKE, [0, 100], [10 ** 9], 0, FAKE, FAKE)
     expect(1, kv.kvc_global_select_static, P(), FAKE, [0, 100], [10], 0, 0, FAKE)
+
+
+def test_bench_traffic_file_is_tied_to_the_kernel_sources(tmp_path, monkeypatch):
+    """bench.py hands out counter-derived HBM bytes only while the kernel sources still
+    have the digest the figures were recorded with."""
+    import importlib.util
+    import json
+    spec = importlib.util.spec_from_file_location("kvc_bench", os.path.join(ROOT, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    shape = {"hq": 32, "hkv": 8, "head_dim": 128, "window": 64, "tokens": 131072}
+    good = {"commit": "abc", "kernel_source_digest": bench.kernel_source_digest(), "layer_shape": shape,
+            "fetch_scale": 2.0, "write_scale": 1.0,
+            "kernels": {"score_mfma<stats>": {"bytes_per_layer": 274.3e6}}}
+    f = tmp_path / "t.json"
+    monkeypatch.setattr(bench, "TRAFFIC_FILE", str(f))
+    assert bench.load_traffic("score_mfma<stats>", shape)[0] is None          # no file
+    f.write_text(json.dumps(good))
+    per_layer, note = bench.load_traffic("score_mfma<stats>", shape)
+    assert per_layer == 274.3e6 and "abc" in note
+    assert bench.load_traffic("score_mfma<emit>", shape)[0] is None           # kernel not recorded
+    assert bench.load_traffic("score_mfma<stats>", dict(shape, tokens=1))[0] is None
+    f.write_text(json.dumps(dict(good, kernel_source_digest="0" * 16)))
+    per_layer, note = bench.load_traffic("score_mfma<stats>", shape)
+    assert per_layer is None and "stale" in note

@@ -416,3 +416,21 @@ def test_score_stats_reference_overflow_rerun(kind):
     # error seen (2.7e-5) is that of fp32 logits themselves
     np.testing.assert_allclose(got[big], ref[big], rtol=1e-4)
     assert np.all(got[~big] <= 1e-29)
+
+
+# ------------------------------------------------------------------ measurement aids
+@pytest.mark.parametrize("mode", [0, 1])
+def test_mfma_probe_runs_and_reports(mode):
+    _say(f"mfma probe mode {mode}")
+    ops = torch.randn(kv.KVC_MFMA_PROBE_OPERAND_BYTES // 2, device="cuda").to(torch.bfloat16)
+    sink = torch.full((kv.KVC_MFMA_PROBE_SINK_FLOATS,), float("nan"), device="cuda")
+    cycles = torch.zeros(2, dtype=torch.int64, device="cuda")
+    flops = kv.kvc_mfma_probe(ops.data_ptr(), 200, mode, sink.data_ptr(), cycles.data_ptr(), stream())
+    torch.cuda.synchronize()
+    # 512 workgroups x 4 waves x 200 iterations x 16 MFMAs of 32x32x16
+    assert flops == 512 * 4 * 200 * 16 * 2 * 32 * 32 * 16
+    assert bool(torch.isfinite(sink).all())
+    c = cycles.cpu().numpy()
+    assert c[0] > 200 * 16 * 32 and c[1] > 0          # at least the matrix-pipe time of one wave
+    with pytest.raises(kv.KvcError):
+        kv.kvc_mfma_probe(ops.data_ptr(), 0, mode, sink.data_ptr(), 0, stream())
