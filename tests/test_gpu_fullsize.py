@@ -1,4 +1,4 @@
-"""Full-size checks of the BASELINE workloads in the launch configuration bench.py
+"""Full-size checks of the benchmark workloads in the launch configuration bench.py
 times (config 2 is the benchmarked one; 1, 3 and 4 exercise the 32k shape, the packed
 variable-length batch and the deep GQA-8 shape with row chunks).
 
