@@ -76,11 +76,10 @@
  * d * sizeof(element) a multiple of 16 bytes and d <= 256.  The sequence table and
  * the per-layer pointer tables travel to the kernels as by-value arguments (no device
  * copy, no allocation, nothing to keep alive), and a kernel's argument block holds
- * 4 KB: hence 64 sequences and 128 layers per call.  Sequences of a batch are
- * independent (own budget, own threshold), so a larger batch is compressed as several
- * calls of at most 64 sequences each with identical results; at the 4096-token
- * contexts of the paper's evaluation one call of 64 sequences already fills the GPU
- * (8192 rank segments, 16384 score workgroups per pass at the 8B shape).
+ * 4 KB: hence 256 sequences and 128 layers per call (the largest argument block is
+ * 3.4 KB).  Sequences of a batch are independent (own budget, own threshold), so a
+ * larger batch is compressed as several calls with identical results; at the
+ * 4096-token contexts of the paper's evaluation 256 sequences are a million tokens.
  */
 #ifndef KVC_H
 #define KVC_H
@@ -92,7 +91,7 @@
 extern "C" {
 #endif
 
-#define KVC_MAX_BATCH 64
+#define KVC_MAX_BATCH 256
 #define KVC_MAX_LAYERS 128
 
 typedef enum {

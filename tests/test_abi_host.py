@@ -68,7 +68,7 @@ def test_invalid_params(bad):
 
 
 @pytest.mark.parametrize("bad", [
-    dict(head_dim=12), dict(head_dim=512), dict(batch=65), dict(layers=129), dict(window=5000)])
+    dict(head_dim=12), dict(head_dim=512), dict(batch=257), dict(layers=129), dict(window=5000)])
 def test_unsupported_params(bad):
     expect(2, kv.kvc_workspace_size, P(**bad), 100, 100)
 

@@ -289,6 +289,8 @@ E2E_CASES = {
     "config7-qwen3-14b-4k": (7, dict(layers=2, batch=2), None),
     # an empty sequence between two others (its budget is 0; nothing is written for it)
     "config3-empty-sequence-inside": (3, dict(layers=2, batch=3, n_range=(300, 900)), [700, 0, 450]),
+    # a batch of 200 short sequences (the sequence table travels as a kernel argument)
+    "config3-batch-200": (3, dict(layers=1, batch=200, n_range=(40, 300)), None),
 }
 
 
