@@ -57,9 +57,10 @@ def log(msg):
 
 # --------------------------------------------------------------------------- traffic file
 def kernel_source_digest() -> str:
-    """sha256 over the kernel sources (names and contents, sorted)."""
+    """sha256 over the kernel sources and the C header (names and contents, sorted)."""
     h = hashlib.sha256()
-    for path in sorted(glob.glob(os.path.join(KERNEL_DIR, "*"))):
+    for path in sorted(glob.glob(os.path.join(KERNEL_DIR, "*")) +
+                       glob.glob(os.path.join(ROOT, "include", "*.h"))):
         if os.path.isfile(path):
             h.update(os.path.basename(path).encode())
             h.update(open(path, "rb").read())

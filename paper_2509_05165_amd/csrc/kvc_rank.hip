@@ -187,34 +187,34 @@ __device__ __forceinline__ void radix_pass(RankShared& sh, int n, const float* _
       __builtin_amdgcn_wave_barrier();
     }
     lds_barrier();
-    // wave 0, lane l owns digits 4l..4l+3: per-wave counts -> prefixes inside the
-    // digit, digit totals -> tile-local start slots and the global base
-    if (wave == 0) {
-      uint32_t run[4] = {0, 0, 0, 0};
+    // threads 0..255 own one digit each: per-wave counts -> prefixes inside the digit,
+    // digit totals -> tile-local start slots and the global base (four waves in
+    // parallel, conflict-free columns; one wave doing it alone took 1 us per tile)
+    uint32_t mine = 0, local_start = 0;
+    if (tid < RK_BINS) {
 #pragma unroll
       for (int w = 0; w < RK_WAVES; ++w) {
-        uint4* cell = reinterpret_cast<uint4*>(&sh.wave_cnt[w][4 * lane]);
-        const uint4 c = *cell;
-        *cell = make_uint4(run[0], run[1], run[2], run[3]);
-        run[0] += c.x; run[1] += c.y; run[2] += c.z; run[3] += c.w;
+        const uint32_t c = sh.wave_cnt[w][tid];
+        sh.wave_cnt[w][tid] = mine;              // items of this digit in the waves before w
+        mine += c;
       }
-      const uint32_t mine = run[0] + run[1] + run[2] + run[3];
       uint32_t incl = mine;
 #pragma unroll
       for (int off = 1; off < 64; off <<= 1) {
         const uint32_t o = __shfl_up(incl, off);
         if (lane >= off) incl += o;
       }
-      uint32_t start = incl - mine;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int d = 4 * lane + j;
-        const uint32_t g = sh.bucket[d];
-        sh.tstart[d] = start;
-        sh.gbase[d] = g - start;
-        sh.bucket[d] = g + run[j];
-        start += run[j];
-      }
+      local_start = incl - mine;                 // exclusive within the wave
+      if (lane == 63) sh.wave_tot[wave] = incl;  // (free since the bucket scan of the pass start)
+    }
+    lds_barrier();
+    if (tid < RK_BINS) {
+      uint32_t start = local_start;
+      for (int w = 0; w < wave; ++w) start += sh.wave_tot[w];
+      const uint32_t g = sh.bucket[tid];
+      sh.tstart[tid] = start;
+      sh.gbase[tid] = g - start;
+      sh.bucket[tid] = g + mine;
     }
     lds_barrier();
     // every item goes to its tile-local slot
