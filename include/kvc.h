@@ -72,7 +72,7 @@
  * except KVC_ERR_HIP which reports a failed launch (kvc_last_error() has the
  * HIP message).  No function aborts or throws.
  *
- * Limits: Bt <= KVC_MAX_BATCH, Lyr <= KVC_MAX_LAYERS, T < 2^30,
+ * Limits: Bt <= KVC_MAX_BATCH, Lyr <= KVC_MAX_LAYERS, T < 2^30, every N_b < 2^29,
  * d * sizeof(element) a multiple of 16 bytes and d <= 256.  The sequence table and
  * the per-layer pointer tables travel to the kernels as by-value arguments (no device
  * copy, no allocation, nothing to keep alive), and a kernel's argument block holds

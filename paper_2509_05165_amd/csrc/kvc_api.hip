@@ -114,6 +114,9 @@ static kvc_status make_problem(const kvc_params* p, const int64_t* cu, Problem* 
   if (cu[p->batch] >= (int64_t(1) << 30)) {
     set_error("total tokens must be below 2^30"); return KVC_ERR_UNSUPPORTED;
   }
+  if (mx >= (int64_t(1) << 29)) {   // 8-byte items of one sequence are addressed with 32-bit byte offsets
+    set_error("every sequence must be shorter than 2^29 tokens"); return KVC_ERR_UNSUPPORTED;
+  }
   pb->batch = p->batch; pb->layers = p->layers; pb->hq = p->hq; pb->hkv = p->hkv;
   pb->group = p->hq / p->hkv; pb->d = p->head_dim; pb->window = p->window;
   pb->dtype = p->dtype; pb->agg_task = p->agg_task; pb->agg_group = p->agg_group;

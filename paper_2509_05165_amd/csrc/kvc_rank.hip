@@ -1,12 +1,23 @@
 // kvc_head_rank: per (layer, KV head, sequence) stable descending argsort of
 // the scores (Section 3.3, eq. 17) and the rank-aligned scores S'.
 //
-// One workgroup sorts one segment with a least-significant-digit radix sort,
-// 8 bits per pass, on the order-preserving integer image of the fp32 scores
-// (inverted, so that ascending keys are descending scores).  LSD passes are
-// stable, which yields the ascending-index order of equal scores for free.
-// Within a tile every wave ranks its items with ballot-based digit matching
-// and lane prefix counts; per-wave digit counters live in LDS.
+// One workgroup sorts one segment with a least-significant-digit radix sort on
+// the order-preserving integer image of the fp32 scores (inverted, so that
+// ascending keys are descending scores).  LSD passes are stable, which yields
+// the ascending-index order of equal scores for free.
+//
+// The number of passes follows the data.  A first sweep over the segment counts
+// the lowest digit and the top byte of every key; the span of the top bytes says
+// how many key bits differ at all once the smallest top byte is subtracted.
+// Scores are positive and span some tens of binades, so 26..30 bits matter:
+// three passes of 9 bits (span below 2^27) or of 10 bits (below 2^30) replace
+// four passes of 8; anything wider (mixed signs) takes four passes of 9 bits.
+// The digit counts of pass p+1 are taken while pass p runs.
+//
+// Between the passes the items travel as (key, position) pairs of 8 bytes, so
+// a run of equal digits is one contiguous stretch of memory, written with one
+// store per item.  Within a tile every wave ranks its items with ballot-based
+// digit matching and lane prefix counts; per-wave digit counters live in LDS.
 //
 // A segment that fits one tile (n <= 8192) never leaves the chip between the
 // passes: the digit-ordered staging area of one pass is the input of the next,
@@ -21,7 +32,9 @@ constexpr int RK_THREADS = 1024;
 constexpr int RK_WAVES = RK_THREADS / 64;
 constexpr int RK_ITEMS = 8;
 constexpr int RK_TILE = RK_THREADS * RK_ITEMS;
-constexpr int RK_BINS = 256;
+constexpr int RK_SHORT_TILE = RK_THREADS * 4;
+constexpr int RK_MAX_BINS = 1024;          // 10-bit digits at most
+static_assert(RK_MAX_BINS <= RK_THREADS, "one thread per bin in the scans");
 
 __device__ __forceinline__ uint32_t desc_key(float f) { return ~float_to_ordered(f); }
 __device__ __forceinline__ float desc_key_to_float(uint32_t k) { return ordered_to_float(~k); }
@@ -40,17 +53,18 @@ __device__ __forceinline__ T* uniform_ptr(T* p) {
   return (T*)reinterpret_cast<global_ptr>(((uint64_t)hi << 32) | lo);
 }
 
-// Element `i` of a 4-byte array through a 32-bit byte offset (the library limits
-// T to 2^30 tokens, so 4*i fits): scalar base + 32-bit lane offset addressing.
+// Element `i` of an array of 4- or 8-byte elements through a 32-bit byte offset
+// (segments are shorter than 2^29 items, so 8*i fits): scalar base + 32-bit lane
+// offset addressing.
 template <typename T>
 __device__ __forceinline__ T& at32(T* base, uint32_t i) {
-  static_assert(sizeof(T) == 4, "4-byte elements");
-  return *reinterpret_cast<T*>(reinterpret_cast<char*>(base) + (i << 2));
+  static_assert(sizeof(T) == 4 || sizeof(T) == 8, "4- or 8-byte elements");
+  return *reinterpret_cast<T*>(reinterpret_cast<char*>(base) + (i * (uint32_t)sizeof(T)));
 }
 template <typename T>
 __device__ __forceinline__ const T& at32(const T* base, uint32_t i) {
-  static_assert(sizeof(T) == 4, "4-byte elements");
-  return *reinterpret_cast<const T*>(reinterpret_cast<const char*>(base) + (i << 2));
+  static_assert(sizeof(T) == 4 || sizeof(T) == 8, "4- or 8-byte elements");
+  return *reinterpret_cast<const T*>(reinterpret_cast<const char*>(base) + (i * (uint32_t)sizeof(T)));
 }
 
 // Workgroup barrier that orders LDS traffic only: global stores still in flight
@@ -61,21 +75,22 @@ __device__ __forceinline__ void lds_barrier() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-// lanes (among `valid`) whose 8-bit digit (bits SHIFT..SHIFT+7 of the key) equals
-// mine.  Per bit: `mine` is all ones or all zeros (one signed bit-field extract),
-// the lanes that agree with it are ~(ballot ^ mine); written on 32-bit halves as
-// x & ~(y ^ z), which is one three-input bit operation per half (truth table 0x90:
-// the encoding the compiler itself picks for that expression; spelled out because
-// it otherwise splits it into an xor and a shared three-input and).  Four vector
-// instructions per bit: extract, compare (the ballot), two bit operations.
-template <int SHIFT>
-__device__ __forceinline__ uint64_t match_digit(uint32_t key, uint64_t valid) {
+// lanes (among `valid`) whose W-bit digit (bits 0..W-1 of `skey`, the key already
+// shifted down) equals mine.  Per bit: `mine` is all ones or all zeros (one signed
+// bit-field extract), the lanes that agree with it are ~(ballot ^ mine); written
+// on 32-bit halves as x & ~(y ^ z), which is one three-input bit operation per half
+// (truth table 0x90: the encoding the compiler itself picks for that expression;
+// spelled out because it otherwise splits it into an xor and a shared three-input
+// and).  Four vector instructions per bit: extract, compare (the ballot), two bit
+// operations.
+template <int W>
+__device__ __forceinline__ uint64_t match_digit(uint32_t skey, uint64_t valid) {
   uint32_t lo = (uint32_t)valid, hi = (uint32_t)(valid >> 32);
 #pragma unroll
-  for (int bit = 0; bit < 8; ++bit) {
+  for (int bit = 0; bit < W; ++bit) {
     // (spelled as the instruction: the builtin is lowered to a shift pair)
     uint32_t mine;
-    asm("v_bfe_i32 %0, %1, %2, 1" : "=v"(mine) : "v"(key), "n"(SHIFT + bit));
+    asm("v_bfe_i32 %0, %1, %2, 1" : "=v"(mine) : "v"(skey), "n"(bit));
     const uint64_t bal = __ballot(mine != 0u);
     lo = __builtin_amdgcn_bitop3_b32(lo, (uint32_t)bal, mine, 0x90);
     hi = __builtin_amdgcn_bitop3_b32(hi, (uint32_t)(bal >> 32), mine, 0x90);
@@ -88,39 +103,53 @@ __device__ __forceinline__ int lanes_below(uint64_t mask) {
                                    __builtin_amdgcn_mbcnt_lo(uint32_t(mask), 0));
 }
 
+// LDS of one workgroup, for digits of up to MAXBINS values and tiles of up to TILE
+// items: 148 KB for (1024, 8192), one workgroup per compute unit; 74 KB for
+// (512, 4096), the launch for batches of short sequences, where two workgroups
+// share a compute unit and hide each other's barriers and load latencies.
+template <int MAXBINS, int TILE>
 struct RankShared {
-  uint32_t hist[4][RK_BINS];
-  uint32_t bucket[RK_BINS];            // next free global slot of each digit
-  uint32_t wave_cnt[RK_WAVES][RK_BINS];
-  uint32_t tstart[RK_BINS];            // first tile-local slot of each digit
-  uint32_t gbase[RK_BINS];             // global slot of an item = gbase[digit] + tile-local slot
-  uint32_t wave_tot[4];
-  uint32_t stage_k[RK_TILE];           // the tile in digit order, so that the
-  int32_t stage_v[RK_TILE];            // global writes run over consecutive slots
-};
+  static constexpr int max_bins = MAXBINS;
+  static constexpr int tile = TILE;
+  uint32_t hist[2][MAXBINS];           // digit counts of the running pass and of the next one
+  uint32_t bucket[MAXBINS];            // next free global slot of each digit
+  uint32_t wave_cnt[RK_WAVES][MAXBINS];
+  uint32_t tstart[MAXBINS];            // first tile-local slot of each digit
+  uint32_t gbase[MAXBINS];             // global slot of an item = gbase[digit] + tile-local slot
+  uint32_t wave_tot[RK_WAVES];
+  uint32_t top_min, top_max;           // smallest / largest top byte of the segment's keys
+  uint2 stage[TILE];                   // the tile as (key, position) in digit order, so that
+};                                     // the global writes run over consecutive slots
 
-// One stable counting pass on digit PASS of a segment of n items.  PASS 0 reads
-// the scores themselves (key = inverted ordered image, value = position), the
-// last pass writes scores and positions; the others move (key, value) pairs.
-// Tiles are processed in order; item (wave w, slot e, lane l) of a tile is
-// element base + w*64*ITEMS + e*64 + l, which is also its order inside the tile.
+enum { RK_FIRST = 0, RK_MIDDLE = 1, RK_LAST = 2 };
+
+// One stable counting pass on the W-bit digit at bit `shift` of a segment of n
+// items; hist[hsel] holds the digit counts, and unless this is the last pass the
+// counts of the next digit are gathered into hist[hsel ^ 1] on the way.  The first
+// pass reads the scores themselves (key = inverted ordered image minus `rebase`,
+// value = position), the last one writes scores and positions; in between (key,
+// value) pairs move.  Tiles are processed in order; item (wave w, slot e, lane l)
+// of a tile is element base + w*64*ITEMS + e*64 + l, which is also its order
+// inside the tile.
 // LIN / LOUT (single-tile segments only): the pass reads its (key, value) pairs
 // from / leaves them in the LDS staging area, in slot order.
-template <int PASS, bool LIN, bool LOUT, int ITEMS>
-__device__ __forceinline__ void radix_pass(RankShared& sh, int n, const float* __restrict__ src_f,
-                                           const uint32_t* __restrict__ src_k,
-                                           const int32_t* __restrict__ src_i,
-                                           uint32_t* __restrict__ dst_k,
-                                           int32_t* __restrict__ dst_i,
-                                           float* __restrict__ dst_f) {
-  constexpr int shift = PASS * 8;
+template <int W, int KIND, bool LIN, bool LOUT, int ITEMS, typename SH>
+__device__ __forceinline__ void radix_pass(SH& sh, int n, int shift, int hsel,
+                                           uint32_t rebase, const float* __restrict__ src_f,
+                                           const uint2* __restrict__ src_p,
+                                           uint2* __restrict__ dst_p, float* __restrict__ dst_f,
+                                           int32_t* __restrict__ dst_i) {
+  constexpr int BINS = 1 << W;
+  constexpr uint32_t DMASK = BINS - 1;
   constexpr int TILE = RK_THREADS * ITEMS;
+  static_assert(BINS <= SH::max_bins && BINS % 64 == 0 && TILE <= SH::tile, "digit width, tile size");
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  src_f = uniform_ptr(src_f); src_k = uniform_ptr(src_k); src_i = uniform_ptr(src_i);
-  dst_k = uniform_ptr(dst_k); dst_i = uniform_ptr(dst_i); dst_f = uniform_ptr(dst_f);
-  // exclusive scan of hist[PASS] -> bucket (first 256 threads = 4 waves)
-  if (tid < RK_BINS) {
-    const uint32_t c = sh.hist[PASS][tid];
+  src_f = uniform_ptr(src_f); src_p = uniform_ptr(src_p);
+  dst_p = uniform_ptr(dst_p); dst_i = uniform_ptr(dst_i); dst_f = uniform_ptr(dst_f);
+  // exclusive scan of hist[hsel] -> bucket (one thread per bin); the other
+  // histogram is cleared for the counts of the next digit
+  if (tid < BINS) {
+    const uint32_t c = sh.hist[hsel][tid];
     uint32_t incl = c;
 #pragma unroll
     for (int off = 1; off < 64; off <<= 1) {
@@ -130,8 +159,9 @@ __device__ __forceinline__ void radix_pass(RankShared& sh, int n, const float* _
     if (lane == 63) sh.wave_tot[wave] = incl;
     sh.bucket[tid] = incl - c;   // exclusive within the wave
   }
+  if (tid < SH::max_bins) sh.hist[hsel ^ 1][tid] = 0;
   __syncthreads();
-  if (tid < RK_BINS) {
+  if (tid < BINS) {
     uint32_t add = 0;
     for (int w = 0; w < wave; ++w) add += sh.wave_tot[w];
     sh.bucket[tid] += add;
@@ -146,9 +176,11 @@ __device__ __forceinline__ void radix_pass(RankShared& sh, int n, const float* _
   _Pragma("unroll") for (int e = 0; e < ITEMS; ++e) {       \
     const int pos = (BASE) + woff + e * 64;                    \
     const uint32_t cpos = uint32_t(pos < n ? pos : n - 1);     /* unsigned: 32-bit offset addressing */ \
-    if (PASS == 0) { K[e] = __float_as_uint(at32(src_f, cpos)); V[e] = int32_t(cpos); } \
-    else if (LIN) { K[e] = sh.stage_k[cpos]; V[e] = sh.stage_v[cpos]; }  \
-    else { K[e] = at32(src_k, cpos); V[e] = at32(src_i, cpos); }           \
+    if (KIND == RK_FIRST) { K[e] = __float_as_uint(at32(src_f, cpos)); V[e] = int32_t(cpos); } \
+    else {                                                      \
+      const uint2 kv_ = LIN ? sh.stage[cpos] : at32(src_p, cpos); \
+      K[e] = kv_.x; V[e] = int32_t(kv_.y);                      \
+    }                                                           \
   }
   KVC_RANK_LOAD_TILE(0, key, val)
   // (explicit, so that the loop body starts with no load the compiler still has to
@@ -159,39 +191,40 @@ __device__ __forceinline__ void radix_pass(RankShared& sh, int n, const float* _
     // next tile's loads fly while this one is ranked and scattered
     const int nbase = base + TILE < n ? base + TILE : base;
     if (!LIN && !LOUT) { KVC_RANK_LOAD_TILE(nbase, nkey, nval) }   // a single tile has no next one
-    if (PASS == 0) {
+    if (KIND == RK_FIRST) {
 #pragma unroll
-      for (int e = 0; e < ITEMS; ++e) key[e] = desc_key(__uint_as_float(key[e]));
+      for (int e = 0; e < ITEMS; ++e) key[e] = desc_key(__uint_as_float(key[e])) - rebase;
     }
 
     uint32_t rank[ITEMS];
     const int wbase = base + woff;
     // zero this wave's counters (only this wave touches them until the barrier)
 #pragma unroll
-    for (int i = 0; i < RK_BINS / 64; ++i) sh.wave_cnt[wave][i * 64 + lane] = 0;
+    for (int i = 0; i < BINS / 64; ++i) sh.wave_cnt[wave][i * 64 + lane] = 0;
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
     for (int e = 0; e < ITEMS; ++e) {
       const bool valid = wbase + e * 64 < n;
       const uint64_t vmask = __ballot(valid);
-      const uint32_t digit = (key[e] >> shift) & 255u;
-      const uint64_t mask = match_digit<shift>(key[e], vmask);
+      const uint32_t skey = key[e] >> shift;
+      const uint32_t digit = skey & DMASK;
+      const uint64_t mask = match_digit<W>(skey, vmask);
       const int below = lanes_below(mask);
       uint32_t prev = 0;
       if (valid) prev = sh.wave_cnt[wave][digit];
       rank[e] = prev + below;
       __builtin_amdgcn_wave_barrier();
       if (valid && below == 0) sh.wave_cnt[wave][digit] = prev + (uint32_t)__popcll(mask);
+      if (KIND != RK_LAST && valid) atomicAdd(&sh.hist[hsel ^ 1][(skey >> W) & DMASK], 1u);
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
     }
     lds_barrier();
-    // threads 0..255 own one digit each: per-wave counts -> prefixes inside the digit,
-    // digit totals -> tile-local start slots and the global base (four waves in
-    // parallel, conflict-free columns; one wave doing it alone took 1 us per tile)
+    // one thread per digit: per-wave counts -> prefixes inside the digit, digit
+    // totals -> tile-local start slots and the global base (conflict-free columns)
     uint32_t mine = 0, local_start = 0;
-    if (tid < RK_BINS) {
+    if (tid < BINS) {
 #pragma unroll
       for (int w = 0; w < RK_WAVES; ++w) {
         const uint32_t c = sh.wave_cnt[w][tid];
@@ -208,7 +241,7 @@ __device__ __forceinline__ void radix_pass(RankShared& sh, int n, const float* _
       if (lane == 63) sh.wave_tot[wave] = incl;  // (free since the bucket scan of the pass start)
     }
     lds_barrier();
-    if (tid < RK_BINS) {
+    if (tid < BINS) {
       uint32_t start = local_start;
       for (int w = 0; w < wave; ++w) start += sh.wave_tot[w];
       const uint32_t g = sh.bucket[tid];
@@ -221,10 +254,9 @@ __device__ __forceinline__ void radix_pass(RankShared& sh, int n, const float* _
 #pragma unroll
     for (int e = 0; e < ITEMS; ++e) {
       if (wbase + e * 64 < n) {
-        const uint32_t digit = (key[e] >> shift) & 255u;
+        const uint32_t digit = (key[e] >> shift) & DMASK;
         const uint32_t slot = sh.tstart[digit] + sh.wave_cnt[wave][digit] + rank[e];
-        sh.stage_k[slot] = key[e];
-        sh.stage_v[slot] = val[e];
+        sh.stage[slot] = make_uint2(key[e], uint32_t(val[e]));
       }
     }
     lds_barrier();
@@ -245,15 +277,15 @@ __device__ __forceinline__ void radix_pass(RankShared& sh, int n, const float* _
     for (int e = 0; e < ITEMS; ++e) {
       const int slot = e * RK_THREADS + tid;
       if (slot < tile_n) {
-        const uint32_t k = sh.stage_k[slot];
-        const int32_t v = sh.stage_v[slot];
-        const uint32_t dst = sh.gbase[(k >> shift) & 255u] + (uint32_t)slot;
-        if (PASS == 3) {
-          at32(dst_f, dst) = desc_key_to_float(k);
-          at32(dst_i, dst) = v;
-        } else {
-          at32(dst_k, dst) = k;
-          at32(dst_i, dst) = v;
+        const uint2 kv = sh.stage[slot];
+        const uint32_t dst = sh.gbase[(kv.x >> shift) & DMASK] + (uint32_t)slot;
+        if (dst < (uint32_t)n) {       // always true for consistent counts; keeps a store inside the segment regardless
+          if (KIND == RK_LAST) {
+            at32(dst_f, dst) = desc_key_to_float(kv.x + rebase);
+            at32(dst_i, dst) = int32_t(kv.y);
+          } else {
+            at32(dst_p, dst) = kv;
+          }
         }
       }
     }
@@ -265,34 +297,48 @@ __device__ __forceinline__ void radix_pass(RankShared& sh, int n, const float* _
   __syncthreads();
 }
 
-// grid: (layers * hkv, batch); block: RK_THREADS.  One workgroup sorts one
-// segment: 4 stable passes of 8 bits, ping-pong between the workspace pair
-// (tmp_keys, tmp_idx) and the output arrays.
+// All passes of one segment with W-bit digits.  Multi-tile segments ping-pong
+// between the two pair arrays of the workspace; a single tile stays in LDS.
+template <int W, bool ONE_TILE, int ITEMS, typename SH>
+__device__ __forceinline__ void radix_sort(SH& sh, int n, int passes, uint32_t rebase,
+                                           const float* src_f, uint2* pa, uint2* pb, float* out_f,
+                                           int32_t* out_i) {
+  radix_pass<W, RK_FIRST, false, ONE_TILE, ITEMS>(sh, n, 0, 0, rebase, src_f, nullptr, pa, nullptr, nullptr);
+  int p = 1;
+  for (; p < passes - 1; ++p) {
+    radix_pass<W, RK_MIDDLE, ONE_TILE, ONE_TILE, ITEMS>(sh, n, p * W, p & 1, rebase, nullptr, pa, pb, nullptr, nullptr);
+    uint2* t = pa; pa = pb; pb = t;
+  }
+  radix_pass<W, RK_LAST, ONE_TILE, false, ITEMS>(sh, n, p * W, p & 1, rebase, nullptr, pa, nullptr, out_f, out_i);
+}
+
+// grid: (layers * hkv, batch); block: RK_THREADS.  One workgroup sorts one segment.
+// SHORT: every segment of the launch has at most RK_SHORT_TILE items (the host
+// checks the longest sequence); a longer one is left alone.
+template <bool SHORT>
 __global__ __launch_bounds__(RK_THREADS) void head_rank_kernel(
     const float* __restrict__ S, SeqTable seq, int total, int32_t* __restrict__ idx_out,
-    float* __restrict__ sorted_out, uint32_t* __restrict__ tmp_keys,
-    int32_t* __restrict__ tmp_idx) {
-  __shared__ RankShared sh;
+    float* __restrict__ sorted_out, uint2* __restrict__ pairs_a, uint2* __restrict__ pairs_b) {
+  typedef RankShared<SHORT ? 512 : RK_MAX_BINS, SHORT ? RK_SHORT_TILE : RK_TILE> Shared;
+  __shared__ Shared sh;
   const int b = blockIdx.y;
   const int n = seq.cu[b + 1] - seq.cu[b];
-  if (n == 0) return;
+  if (n == 0 || (SHORT && n > RK_SHORT_TILE)) return;
   const size_t seg = (size_t)blockIdx.x * total + seq.cu[b];
   const float* src_f = S + seg;
-  uint32_t* a_keys = tmp_keys + seg;
-  int32_t* a_idx = tmp_idx + seg;
-  uint32_t* b_keys = reinterpret_cast<uint32_t*>(sorted_out) + seg;
-  int32_t* b_idx = idx_out + seg;
   const int tid = threadIdx.x;
 
-  // ---- histograms of all four digits in one sweep ----
-  // Eight loads in flight per thread.  The top digit (sign and high exponent bits)
-  // takes three or four values in a whole segment, so its atomics would all hit one
-  // address; it is counted in 32 bank-private copies instead, which live in the
+  // ---- counts of the lowest digit (as wide as the histogram allows: folded below if
+  // the passes use fewer bits) and of the top byte, in one sweep ----
+  // Eight loads in flight per thread.  The top byte (sign and high exponent bits)
+  // takes a handful of values in a whole segment, so its atomics would all hit a few
+  // addresses; it is counted in 32 bank-private copies instead, which live in the
   // staging area (unused until the first pass) and are summed afterwards.
-  static_assert(RK_TILE >= RK_BINS * 32, "staging area holds the 32 copies");
-  uint32_t* top_copies = sh.stage_k;
-  for (int i = tid; i < 3 * RK_BINS; i += RK_THREADS) (&sh.hist[0][0])[i] = 0;
-  for (int i = tid; i < RK_BINS * 32; i += RK_THREADS) top_copies[i] = 0;
+  static_assert(Shared::tile * 2 >= 256 * 32, "staging area holds the 32 copies");
+  uint32_t* top_copies = reinterpret_cast<uint32_t*>(sh.stage);
+  if (tid < Shared::max_bins) sh.hist[0][tid] = 0;
+  for (int i = tid; i < 256 * 32; i += RK_THREADS) top_copies[i] = 0;
+  if (tid == 0) { sh.top_min = 255u; sh.top_max = 0u; }
   __syncthreads();
   {
     const float* sweep_f = uniform_ptr(src_f);
@@ -308,40 +354,51 @@ __global__ __launch_bounds__(RK_THREADS) void head_rank_kernel(
       for (int e = 0; e < 8; ++e) {
         if (i0 + e * RK_THREADS + tid < n) {
           const uint32_t key = desc_key(x[e]);
-          atomicAdd(&sh.hist[0][key & 255u], 1u);
-          atomicAdd(&sh.hist[1][(key >> 8) & 255u], 1u);
-          atomicAdd(&sh.hist[2][(key >> 16) & 255u], 1u);
+          atomicAdd(&sh.hist[0][key & (Shared::max_bins - 1)], 1u);
           atomicAdd(&top_copies[(key >> 24) * 32 + bank], 1u);
         }
       }
     }
   }
   __syncthreads();
-  if (tid < RK_BINS) {
+  if (tid < 256) {
     uint32_t sum = 0;
 #pragma unroll 8
     for (int j = 0; j < 32; ++j) sum += top_copies[tid * 32 + ((j + tid) & 31)];
-    sh.hist[3][tid] = sum;
+    if (sum != 0) { atomicMin(&sh.top_min, (uint32_t)tid); atomicMax(&sh.top_max, (uint32_t)tid); }
+  }
+  __syncthreads();
+  // keys minus (smallest top byte << 24) are below 2^(24 + span_bits)
+  const uint32_t top_min = sh.top_min, span = sh.top_max - top_min;
+  const uint32_t rebase = top_min << 24;
+  const int span_bits = span == 0 ? 0 : 32 - __clz((int)span);
+  const bool ten = span_bits > 3 && span_bits <= 6;      // 28..30 bits: three passes of 10
+  const int passes = span_bits <= 6 ? 3 : 4;             // 9-bit digits otherwise: 27 or 36 bits
+  if (!SHORT && (!ten || n <= RK_TILE)) {                // (single tiles always take 9-bit digits)
+    // fold the 10-bit counts into 9-bit ones (every thread reads and writes its own entries)
+    if (tid < 512) sh.hist[0][tid] += sh.hist[0][tid + 512];
   }
   __syncthreads();
 
+  float* out_f = sorted_out + seg;
+  int32_t* out_i = idx_out + seg;
   // one tile: the passes hand the data on through LDS; short segments take fewer
   // items per lane (an unused item slot costs as much ranking work as a used one)
-#define KVC_RANK_ONE_TILE(ITEMS)                                                                        \
-  do {                                                                                                  \
-    radix_pass<0, false, true, ITEMS>(sh, n, src_f, nullptr, nullptr, nullptr, nullptr, nullptr);       \
-    radix_pass<1, true, true, ITEMS>(sh, n, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr);      \
-    radix_pass<2, true, true, ITEMS>(sh, n, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr);      \
-    radix_pass<3, true, false, ITEMS>(sh, n, nullptr, nullptr, nullptr, nullptr, b_idx, sorted_out + seg); \
-  } while (0)
-  if (n <= RK_THREADS * 2) { KVC_RANK_ONE_TILE(2); return; }
-  if (n <= RK_THREADS * 4) { KVC_RANK_ONE_TILE(4); return; }
-  if (n <= RK_TILE) { KVC_RANK_ONE_TILE(RK_ITEMS); return; }
-#undef KVC_RANK_ONE_TILE
-  radix_pass<0, false, false, RK_ITEMS>(sh, n, src_f, nullptr, nullptr, a_keys, a_idx, nullptr);
-  radix_pass<1, false, false, RK_ITEMS>(sh, n, nullptr, a_keys, a_idx, b_keys, b_idx, nullptr);
-  radix_pass<2, false, false, RK_ITEMS>(sh, n, nullptr, b_keys, b_idx, a_keys, a_idx, nullptr);
-  radix_pass<3, false, false, RK_ITEMS>(sh, n, nullptr, a_keys, a_idx, nullptr, b_idx, sorted_out + seg);
+  if (n <= RK_TILE) {
+    const int p1 = span_bits <= 3 ? 3 : 4;
+    if (n <= RK_THREADS * 2) {
+      radix_sort<9, true, 2>(sh, n, p1, rebase, src_f, nullptr, nullptr, out_f, out_i);
+    } else if (SHORT || n <= RK_THREADS * 4) {
+      radix_sort<9, true, 4>(sh, n, p1, rebase, src_f, nullptr, nullptr, out_f, out_i);
+    } else if constexpr (!SHORT) {
+      radix_sort<9, true, RK_ITEMS>(sh, n, p1, rebase, src_f, nullptr, nullptr, out_f, out_i);
+    }
+    return;
+  }
+  if constexpr (!SHORT) {
+    if (ten) radix_sort<10, false, RK_ITEMS>(sh, n, 3, rebase, src_f, pairs_a + seg, pairs_b + seg, out_f, out_i);
+    else radix_sort<9, false, RK_ITEMS>(sh, n, passes, rebase, src_f, pairs_a + seg, pairs_b + seg, out_f, out_i);
+  }
 }
 
 // grid: (token blocks, layers)
@@ -388,18 +445,25 @@ __global__ __launch_bounds__(256) void composite_plain(const float* __restrict__
 }  // namespace
 
 size_t rank_workspace_bytes(const Problem& pb) {
+  // two arrays of (key, position) pairs
   const size_t lht = size_t(pb.layers) * pb.hkv * size_t(pb.total);
-  return align_up(lht * 4) * 2;
+  return align_up(lht * 8) * 2;
 }
 
 kvc_status launch_head_rank(const Problem& pb, const float* S, int32_t* idx, float* S_sorted,
                             void* ws, hipStream_t stream) {
   const size_t lht = size_t(pb.layers) * pb.hkv * size_t(pb.total);
-  uint32_t* tmp_keys = static_cast<uint32_t*>(ws);
-  int32_t* tmp_idx = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + align_up(lht * 4));
+  // (sequences are shorter than 2^29 tokens: checked with the sequence table)
+  uint2* pairs_a = static_cast<uint2*>(ws);
+  uint2* pairs_b = reinterpret_cast<uint2*>(static_cast<char*>(ws) + align_up(lht * 8));
   dim3 grid(pb.layers * pb.hkv, pb.batch);
-  KVC_LAUNCH("head_rank_kernel", stream, head_rank_kernel<<<grid, RK_THREADS, 0, stream>>>(S, pb.seq, int(pb.total), idx, S_sorted,
-                                                    tmp_keys, tmp_idx));
+  if (pb.max_seqlen <= RK_SHORT_TILE) {
+    KVC_LAUNCH("head_rank_kernel", stream, head_rank_kernel<true><<<grid, RK_THREADS, 0, stream>>>(S, pb.seq, int(pb.total), idx, S_sorted,
+                                                      pairs_a, pairs_b));
+  } else {
+    KVC_LAUNCH("head_rank_kernel", stream, head_rank_kernel<false><<<grid, RK_THREADS, 0, stream>>>(S, pb.seq, int(pb.total), idx, S_sorted,
+                                                      pairs_a, pairs_b));
+  }
   return KVC_OK;
 }
 

@@ -78,6 +78,7 @@ def test_sequence_table_checks():
     expect(1, kv.kvc_composite, p, FAKE, [1, 5, 9], FAKE)            # cu[0] != 0
     expect(1, kv.kvc_composite, p, FAKE, [0, 9, 5], FAKE)            # decreasing
     expect(2, kv.kvc_composite, p, FAKE, [0, 5, 1 << 31], FAKE)      # too many tokens
+    expect(2, kv.kvc_composite, p, FAKE, [0, 5, 5 + (1 << 29)], FAKE)  # one sequence of 2^29 tokens
     expect(1, kv.kvc_composite, p, 0, [0, 5, 9], FAKE)               # null S_sorted
     expect(1, kv.kvc_composite, p, FAKE, [0, 5, 9], 0)               # null I
 

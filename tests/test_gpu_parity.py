@@ -120,12 +120,24 @@ def _rank_inputs(kind, lyr, hkv, lens, seed):
         s[..., 5::13] = 1e-42
     elif kind == "constant":
         s = np.full((lyr, hkv, total), 0.25, dtype=np.float32)
+    elif kind == "narrow":        # two binades: the fewest key bits differ
+        s = (0.25 + 0.75 * r.random((lyr, hkv, total))).astype(np.float32)
+    elif kind in ("span7", "span8", "span64"):
+        # the top bytes of the keys span exactly 7 / 8 / 64 values: either side of the
+        # borders between the kernel's digit plans (float32 bit patterns 0x3f.., 0x38..,
+        # 0x37..; zero and the smallest negative denormal are 63 and 64 away from 0x3f..)
+        lo = {"span7": 2.0 ** -15, "span8": 2.0 ** -17, "span64": 0.0}[kind]
+        s = (0.5 * r.random((lyr, hkv, total)) ** 8 + 0.5).astype(np.float32)
+        s[..., ::5] = (lo * (1 + r.random((lyr, hkv, (total + 4) // 5)))).astype(np.float32)
+        if kind == "span64":
+            s[..., 1::17] = -1e-45
     return s
 
 
-@pytest.mark.parametrize("kind", ["scores", "ties", "signed", "constant"])
+@pytest.mark.parametrize("kind", ["scores", "ties", "signed", "constant", "narrow", "span7", "span8",
+                                  "span64"])
 @pytest.mark.parametrize("lens", [[1], [63], [2047], [2048, 2049], [4096], [4097], [8192, 8193],
-                                  [9000, 1, 300], [20000], [16384, 16385], [40000]])
+                                  [9000, 1, 300], [3000, 9000], [20000], [16384, 16385], [40000]])
 def test_head_rank_bit_exact(kind, lens):
     _say(f"rank {kind} lens={lens}")
     lyr, hkv = 2, 3
