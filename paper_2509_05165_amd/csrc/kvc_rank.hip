@@ -30,8 +30,9 @@ namespace {
 
 constexpr int RK_THREADS = 1024;
 constexpr int RK_WAVES = RK_THREADS / 64;
-constexpr int RK_ITEMS = 8;
-constexpr int RK_TILE = RK_THREADS * RK_ITEMS;
+constexpr int RK_ITEMS9 = 12;              // items per lane and tile of a long segment, 9-bit digits
+constexpr int RK_ITEMS10 = 12;             // the same with 10-bit digits (twice the counters in LDS)
+constexpr int RK_TILE = RK_THREADS * RK_ITEMS9;
 constexpr int RK_SHORT_TILE = RK_THREADS * 4;
 constexpr int RK_MAX_BINS = 1024;          // 10-bit digits at most
 static_assert(RK_MAX_BINS <= RK_THREADS, "one thread per bin in the scans");
@@ -67,6 +68,28 @@ __device__ __forceinline__ const T& at32(const T* base, uint32_t i) {
   return *reinterpret_cast<const T*>(reinterpret_cast<const char*>(base) + (i * (uint32_t)sizeof(T)));
 }
 
+// Loads with the streaming (non-temporal) hint, for launches whose segments in
+// flight exceed the caches.  What must stay in the L2 cache during a pass are the
+// partly written lines at the ends of the digit runs, each completed by the next
+// tile some microseconds later; with plain loads the tiles streaming in evict them
+// half written, and the memory sees two partial writes per line (the hint took a
+// three-pass sort of 256 segments of 131072 items from 0.48 to 0.41 ms).  Where
+// the segments in flight fit the 256 MB memory-side cache the hint costs 5-10 %
+// instead (256 segments of 32768 items, batches of shorter ones): a pass then
+// finds what the pass before wrote still cached, and plain loads keep it there.
+constexpr long RK_STREAM_ITEMS = 10L << 20;   // items in flight (longest sequence x workgroups resident) from which loads stream
+template <bool STREAM>
+__device__ __forceinline__ float load_item(const float* p) {
+  return STREAM ? __builtin_nontemporal_load(p) : *p;
+}
+template <bool STREAM>
+__device__ __forceinline__ uint2 load_item(const uint2* p) {
+  typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+  if (!STREAM) return *p;
+  const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(p));
+  return make_uint2(v.x, v.y);
+}
+
 // Workgroup barrier that orders LDS traffic only: global stores still in flight
 // (the scatter of the previous tile) are not waited for.
 __device__ __forceinline__ void lds_barrier() {
@@ -98,30 +121,131 @@ __device__ __forceinline__ uint64_t match_digit(uint32_t skey, uint64_t valid) {
   return ((uint64_t)hi << 32) | lo;
 }
 
+// Inclusive prefix sum over the 64 lanes of a wave with data-parallel-primitive
+// moves: shifts by 1, 2, 4, 8 inside each row of 16 lanes (lanes without a source
+// add zero), then the last lane of rows 0 and 2 is added to rows 1 and 3, and lane
+// 31 to rows 2 and 3.  No index registers and no LDS crossbar traffic, unlike a
+// shuffle-based scan.
+__device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t x) {
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x111, 0xf, 0xf, false);   // row_shr:1
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x112, 0xf, 0xf, false);   // row_shr:2
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x114, 0xf, 0xf, false);   // row_shr:4
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x118, 0xf, 0xf, false);   // row_shr:8
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x142, 0xa, 0xf, false);   // row_bcast:15 -> rows 1, 3
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x143, 0xc, 0xf, false);   // row_bcast:31 -> rows 2, 3
+  return x;
+}
+
 __device__ __forceinline__ int lanes_below(uint64_t mask) {
   return __builtin_amdgcn_mbcnt_hi(uint32_t(mask >> 32),
                                    __builtin_amdgcn_mbcnt_lo(uint32_t(mask), 0));
 }
 
-// LDS of one workgroup, for digits of up to MAXBINS values and tiles of up to TILE
-// items: 148 KB for (1024, 8192), one workgroup per compute unit; 74 KB for
-// (512, 4096), the launch for batches of short sequences, where two workgroups
-// share a compute unit and hide each other's barriers and load latencies.
+// LDS of one workgroup during the passes, for digits of MAXBINS values and tiles
+// of up to TILE items.  The tile is as large as LDS allows, because the length of
+// a digit run in the write-out (TILE / MAXBINS items of 8 bytes) is what the
+// memory system's write rate follows: (512, 16384) and (1024, 12288) take 154 and
+// 148 KB, one workgroup per compute unit; the launch for batches of short
+// sequences uses (512, 4096), 58 KB, so that two workgroups share a compute unit
+// and hide each other's barriers and load latencies.  Per-wave digit counts never
+// exceed the tile size and are kept in 16 bits.
 template <int MAXBINS, int TILE>
 struct RankShared {
   static constexpr int max_bins = MAXBINS;
   static constexpr int tile = TILE;
+  static_assert(TILE <= 65535, "16-bit per-wave counters");
+  uint2 stage[TILE];                   // the tile as (key, position) in digit order, so that
+                                       // the global writes run over consecutive slots
   uint32_t hist[2][MAXBINS];           // digit counts of the running pass and of the next one
   uint32_t bucket[MAXBINS];            // next free global slot of each digit
-  uint32_t wave_cnt[RK_WAVES][MAXBINS];
+  uint16_t wave_cnt[RK_WAVES][MAXBINS];
   uint32_t tstart[MAXBINS];            // first tile-local slot of each digit
   uint32_t gbase[MAXBINS];             // global slot of an item = gbase[digit] + tile-local slot
   uint32_t wave_tot[RK_WAVES];
+};
+
+// LDS of the first sweep over a segment (the layout of the passes is chosen from
+// its result and overlays it).
+struct RankSweepShared {
+  uint32_t low[RK_MAX_BINS];           // counts of the lowest 10 key bits
+  uint32_t top[256 * 32];              // counts of the top byte, 32 bank-private copies
   uint32_t top_min, top_max;           // smallest / largest top byte of the segment's keys
-  uint2 stage[TILE];                   // the tile as (key, position) in digit order, so that
-};                                     // the global writes run over consecutive slots
+};
 
 enum { RK_FIRST = 0, RK_MIDDLE = 1, RK_LAST = 2 };
+
+// One tile of a pass, from the items in registers to the tile in digit order in
+// the staging area: every wave ranks its items inside their digit groups, one
+// thread per digit turns the per-wave counts into slots, every item is written to
+// its slot.
+template <int W, int KIND, int ITEMS, typename SH>
+__device__ __forceinline__ void rank_and_stage(SH& sh, const uint32_t (&key)[ITEMS],
+                                               const int32_t (&val)[ITEMS], int n, int wbase,
+                                               int shift, int hsel) {
+  constexpr int BINS = 1 << W;
+  constexpr uint32_t DMASK = BINS - 1;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  uint32_t rank2[(ITEMS + 1) / 2];   // ranks inside the wave's digit groups, two 16-bit halves per register
+  // zero this wave's counters (only this wave touches them until the barrier)
+#pragma unroll
+  for (int i = 0; i < BINS / 128; ++i) reinterpret_cast<uint32_t*>(sh.wave_cnt[wave])[i * 64 + lane] = 0;
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+#pragma unroll
+  for (int e = 0; e < ITEMS; ++e) {
+    const bool valid = wbase + e * 64 < n;
+    const uint64_t vmask = __ballot(valid);
+    const uint32_t skey = key[e] >> shift;
+    const uint32_t digit = skey & DMASK;
+    const uint64_t mask = match_digit<W>(skey, vmask);
+    const int below = lanes_below(mask);
+    uint32_t prev = 0;
+    if (valid) prev = sh.wave_cnt[wave][digit];
+    if (e & 1) rank2[e / 2] |= (prev + below) << 16; else rank2[e / 2] = prev + below;
+    __builtin_amdgcn_wave_barrier();
+    if (valid && below == 0) sh.wave_cnt[wave][digit] = uint16_t(prev + (uint32_t)__popcll(mask));
+    if (KIND != RK_LAST && valid) atomicAdd(&sh.hist[hsel ^ 1][(skey >> W) & DMASK], 1u);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+  }
+  lds_barrier();
+  // one thread per digit: per-wave counts -> prefixes inside the digit, digit
+  // totals -> tile-local start slots and the global base (conflict-free columns)
+  uint32_t mine = 0, local_start = 0;
+  int dtid = tid;                              // (opaque: the addresses of this step are not
+  asm volatile("" : "+v"(dtid));               // worth registers across the ranking loop)
+  if (tid < BINS) {
+#pragma unroll
+    for (int w = 0; w < RK_WAVES; ++w) {
+      const uint32_t c = sh.wave_cnt[w][dtid];
+      sh.wave_cnt[w][dtid] = uint16_t(mine);   // items of this digit in the waves before w
+      mine += c;
+    }
+    const uint32_t incl = wave_inclusive_sum(mine);
+    local_start = incl - mine;                 // exclusive within the wave
+    if (lane == 63) sh.wave_tot[wave] = incl;  // (free since the bucket scan of the pass start)
+  }
+  lds_barrier();
+  if (tid < BINS) {
+    uint32_t start = local_start;
+    for (int w = 0; w < wave; ++w) start += sh.wave_tot[w];
+    const uint32_t g = sh.bucket[dtid];
+    sh.tstart[dtid] = start;
+    sh.gbase[dtid] = g - start;
+    sh.bucket[dtid] = g + mine;
+  }
+  lds_barrier();
+  // every item goes to its tile-local slot
+#pragma unroll
+  for (int e = 0; e < ITEMS; ++e) {
+    if (wbase + e * 64 < n) {
+      const uint32_t digit = (key[e] >> shift) & DMASK;
+      const uint32_t slot = sh.tstart[digit] + sh.wave_cnt[wave][digit] + ((rank2[e / 2] >> (16 * (e & 1))) & 0xffffu);
+      sh.stage[slot] = make_uint2(key[e], KIND == RK_FIRST ? uint32_t(wbase + e * 64) : uint32_t(val[e]));
+    }
+    if (e % 4 == 3) __builtin_amdgcn_sched_barrier(0);   // (four items' temporaries at a time)
+  }
+}
 
 // One stable counting pass on the W-bit digit at bit `shift` of a segment of n
 // items; hist[hsel] holds the digit counts, and unless this is the last pass the
@@ -133,7 +257,7 @@ enum { RK_FIRST = 0, RK_MIDDLE = 1, RK_LAST = 2 };
 // inside the tile.
 // LIN / LOUT (single-tile segments only): the pass reads its (key, value) pairs
 // from / leaves them in the LDS staging area, in slot order.
-template <int W, int KIND, bool LIN, bool LOUT, int ITEMS, typename SH>
+template <int W, int KIND, bool LIN, bool LOUT, int ITEMS, bool STREAM, typename SH>
 __device__ __forceinline__ void radix_pass(SH& sh, int n, int shift, int hsel,
                                            uint32_t rebase, const float* __restrict__ src_f,
                                            const uint2* __restrict__ src_p,
@@ -142,7 +266,7 @@ __device__ __forceinline__ void radix_pass(SH& sh, int n, int shift, int hsel,
   constexpr int BINS = 1 << W;
   constexpr uint32_t DMASK = BINS - 1;
   constexpr int TILE = RK_THREADS * ITEMS;
-  static_assert(BINS <= SH::max_bins && BINS % 64 == 0 && TILE <= SH::tile, "digit width, tile size");
+  static_assert(BINS <= SH::max_bins && BINS % 128 == 0 && TILE <= SH::tile, "digit width, tile size");
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   src_f = uniform_ptr(src_f); src_p = uniform_ptr(src_p);
   dst_p = uniform_ptr(dst_p); dst_i = uniform_ptr(dst_i); dst_f = uniform_ptr(dst_f);
@@ -150,12 +274,7 @@ __device__ __forceinline__ void radix_pass(SH& sh, int n, int shift, int hsel,
   // histogram is cleared for the counts of the next digit
   if (tid < BINS) {
     const uint32_t c = sh.hist[hsel][tid];
-    uint32_t incl = c;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-      const uint32_t o = __shfl_up(incl, off);
-      if (lane >= off) incl += o;
-    }
+    const uint32_t incl = wave_inclusive_sum(c);
     if (lane == 63) sh.wave_tot[wave] = incl;
     sh.bucket[tid] = incl - c;   // exclusive within the wave
   }
@@ -170,15 +289,18 @@ __device__ __forceinline__ void radix_pass(SH& sh, int n, int shift, int hsel,
 
   uint32_t key[ITEMS], nkey[ITEMS];
   int32_t val[ITEMS], nval[ITEMS];
-  const int woff = wave * 64 * ITEMS + lane;
+  // (opaque, so that addresses derived from it are formed where they are used instead of
+  // being kept, and spilled, across the loop over the passes)
+  int woff = wave * 64 * ITEMS + lane;
+  asm volatile("" : "+v"(woff));
   // loads of one tile; positions past the segment re-read its last element
 #define KVC_RANK_LOAD_TILE(BASE, K, V)                         \
   _Pragma("unroll") for (int e = 0; e < ITEMS; ++e) {       \
     const int pos = (BASE) + woff + e * 64;                    \
     const uint32_t cpos = uint32_t(pos < n ? pos : n - 1);     /* unsigned: 32-bit offset addressing */ \
-    if (KIND == RK_FIRST) { K[e] = __float_as_uint(at32(src_f, cpos)); V[e] = int32_t(cpos); } \
+    if (KIND == RK_FIRST) { K[e] = __float_as_uint(load_item<STREAM>(&at32(src_f, cpos))); }  /* value = position, implicit */ \
     else {                                                      \
-      const uint2 kv_ = LIN ? sh.stage[cpos] : at32(src_p, cpos); \
+      const uint2 kv_ = LIN ? sh.stage[cpos] : load_item<STREAM>(&at32(src_p, cpos)); \
       K[e] = kv_.x; V[e] = int32_t(kv_.y);                      \
     }                                                           \
   }
@@ -196,69 +318,8 @@ __device__ __forceinline__ void radix_pass(SH& sh, int n, int shift, int hsel,
       for (int e = 0; e < ITEMS; ++e) key[e] = desc_key(__uint_as_float(key[e])) - rebase;
     }
 
-    uint32_t rank[ITEMS];
     const int wbase = base + woff;
-    // zero this wave's counters (only this wave touches them until the barrier)
-#pragma unroll
-    for (int i = 0; i < BINS / 64; ++i) sh.wave_cnt[wave][i * 64 + lane] = 0;
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-#pragma unroll
-    for (int e = 0; e < ITEMS; ++e) {
-      const bool valid = wbase + e * 64 < n;
-      const uint64_t vmask = __ballot(valid);
-      const uint32_t skey = key[e] >> shift;
-      const uint32_t digit = skey & DMASK;
-      const uint64_t mask = match_digit<W>(skey, vmask);
-      const int below = lanes_below(mask);
-      uint32_t prev = 0;
-      if (valid) prev = sh.wave_cnt[wave][digit];
-      rank[e] = prev + below;
-      __builtin_amdgcn_wave_barrier();
-      if (valid && below == 0) sh.wave_cnt[wave][digit] = prev + (uint32_t)__popcll(mask);
-      if (KIND != RK_LAST && valid) atomicAdd(&sh.hist[hsel ^ 1][(skey >> W) & DMASK], 1u);
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-    }
-    lds_barrier();
-    // one thread per digit: per-wave counts -> prefixes inside the digit, digit
-    // totals -> tile-local start slots and the global base (conflict-free columns)
-    uint32_t mine = 0, local_start = 0;
-    if (tid < BINS) {
-#pragma unroll
-      for (int w = 0; w < RK_WAVES; ++w) {
-        const uint32_t c = sh.wave_cnt[w][tid];
-        sh.wave_cnt[w][tid] = mine;              // items of this digit in the waves before w
-        mine += c;
-      }
-      uint32_t incl = mine;
-#pragma unroll
-      for (int off = 1; off < 64; off <<= 1) {
-        const uint32_t o = __shfl_up(incl, off);
-        if (lane >= off) incl += o;
-      }
-      local_start = incl - mine;                 // exclusive within the wave
-      if (lane == 63) sh.wave_tot[wave] = incl;  // (free since the bucket scan of the pass start)
-    }
-    lds_barrier();
-    if (tid < BINS) {
-      uint32_t start = local_start;
-      for (int w = 0; w < wave; ++w) start += sh.wave_tot[w];
-      const uint32_t g = sh.bucket[tid];
-      sh.tstart[tid] = start;
-      sh.gbase[tid] = g - start;
-      sh.bucket[tid] = g + mine;
-    }
-    lds_barrier();
-    // every item goes to its tile-local slot
-#pragma unroll
-    for (int e = 0; e < ITEMS; ++e) {
-      if (wbase + e * 64 < n) {
-        const uint32_t digit = (key[e] >> shift) & DMASK;
-        const uint32_t slot = sh.tstart[digit] + sh.wave_cnt[wave][digit] + rank[e];
-        sh.stage[slot] = make_uint2(key[e], uint32_t(val[e]));
-      }
-    }
+    rank_and_stage<W, KIND, ITEMS>(sh, key, val, n, wbase, shift, hsel);
     lds_barrier();
     // The tile's items now live in the staging area, so the registers can take the
     // next tile.  The wait is explicit and placed before the scatter: loads and
@@ -270,26 +331,42 @@ __device__ __forceinline__ void radix_pass(SH& sh, int n, int shift, int hsel,
       for (int e = 0; e < ITEMS; ++e) { key[e] = nkey[e]; val[e] = nval[e]; }
     }
     // consecutive threads write consecutive global slots within a digit run
-    // (single tile with LOUT: slot order is the order of this pass; it stays in LDS)
+    // (single tile with LOUT: slot order is the order of this pass; it stays in LDS).
+    // The destination is clamped into the segment: with consistent counts it never
+    // needs to be, and a store can then not leave the segment whatever happens.
     const int tile_n = min(TILE, n - base);
+#define KVC_RANK_WRITE_SLOT(SLOT)                                                  \
+  {                                                                                \
+    const uint2 kv = sh.stage[SLOT];                                               \
+    uint32_t dst = sh.gbase[(kv.x >> shift) & DMASK] + (uint32_t)(SLOT);           \
+    dst = min(dst, (uint32_t)(n - 1));                                             \
+    if (KIND == RK_LAST) {                                                         \
+      at32(dst_f, dst) = desc_key_to_float(kv.x + rebase);                         \
+      at32(dst_i, dst) = int32_t(kv.y);                                            \
+    } else {                                                                       \
+      at32(dst_p, dst) = kv;                                                       \
+    }                                                                              \
+  }
     if (!LOUT) {
+      // (the thread's slot base is made opaque here, so that the sixteen slot addresses
+      // are formed where they are used instead of being kept, and spilled, across the
+      // tile loop; four items at a time keep the temporaries of the write-out few)
+      int stid = tid;
+      asm volatile("" : "+v"(stid));
+      if (tile_n == TILE) {              // a full tile: no per-item bounds
 #pragma unroll
-    for (int e = 0; e < ITEMS; ++e) {
-      const int slot = e * RK_THREADS + tid;
-      if (slot < tile_n) {
-        const uint2 kv = sh.stage[slot];
-        const uint32_t dst = sh.gbase[(kv.x >> shift) & DMASK] + (uint32_t)slot;
-        if (dst < (uint32_t)n) {       // always true for consistent counts; keeps a store inside the segment regardless
-          if (KIND == RK_LAST) {
-            at32(dst_f, dst) = desc_key_to_float(kv.x + rebase);
-            at32(dst_i, dst) = int32_t(kv.y);
-          } else {
-            at32(dst_p, dst) = kv;
-          }
+        for (int e = 0; e < ITEMS; ++e) {
+          KVC_RANK_WRITE_SLOT(e * RK_THREADS + stid)
+          if (e % 4 == 3) __builtin_amdgcn_sched_barrier(0);
+        }
+      } else {
+#pragma unroll
+        for (int e = 0; e < ITEMS; ++e) {
+          if (e * RK_THREADS + stid < tile_n) KVC_RANK_WRITE_SLOT(e * RK_THREADS + stid)
         }
       }
     }
-    }
+#undef KVC_RANK_WRITE_SLOT
   }
 #undef KVC_RANK_LOAD_TILE
   // the next pass reads what this one scattered: full fence + barrier
@@ -299,28 +376,34 @@ __device__ __forceinline__ void radix_pass(SH& sh, int n, int shift, int hsel,
 
 // All passes of one segment with W-bit digits.  Multi-tile segments ping-pong
 // between the two pair arrays of the workspace; a single tile stays in LDS.
-template <int W, bool ONE_TILE, int ITEMS, typename SH>
+template <int W, bool ONE_TILE, int ITEMS, bool STREAM, typename SH>
 __device__ __forceinline__ void radix_sort(SH& sh, int n, int passes, uint32_t rebase,
                                            const float* src_f, uint2* pa, uint2* pb, float* out_f,
                                            int32_t* out_i) {
-  radix_pass<W, RK_FIRST, false, ONE_TILE, ITEMS>(sh, n, 0, 0, rebase, src_f, nullptr, pa, nullptr, nullptr);
+  radix_pass<W, RK_FIRST, false, ONE_TILE, ITEMS, STREAM>(sh, n, 0, 0, rebase, src_f, nullptr, pa, nullptr, nullptr);
   int p = 1;
   for (; p < passes - 1; ++p) {
-    radix_pass<W, RK_MIDDLE, ONE_TILE, ONE_TILE, ITEMS>(sh, n, p * W, p & 1, rebase, nullptr, pa, pb, nullptr, nullptr);
+    radix_pass<W, RK_MIDDLE, ONE_TILE, ONE_TILE, ITEMS, STREAM>(sh, n, p * W, p & 1, rebase, nullptr, pa, pb, nullptr, nullptr);
     uint2* t = pa; pa = pb; pb = t;
   }
-  radix_pass<W, RK_LAST, ONE_TILE, false, ITEMS>(sh, n, p * W, p & 1, rebase, nullptr, pa, nullptr, out_f, out_i);
+  radix_pass<W, RK_LAST, ONE_TILE, false, ITEMS, STREAM>(sh, n, p * W, p & 1, rebase, nullptr, pa, nullptr, out_f, out_i);
 }
 
 // grid: (layers * hkv, batch); block: RK_THREADS.  One workgroup sorts one segment.
 // SHORT: every segment of the launch has at most RK_SHORT_TILE items (the host
-// checks the longest sequence); a longer one is left alone.
-template <bool SHORT>
+// checks the longest sequence); a longer one is left alone.  STREAM: the loads of
+// multi-tile segments carry the streaming hint.
+template <bool SHORT, bool STREAM>
 __global__ __launch_bounds__(RK_THREADS) void head_rank_kernel(
     const float* __restrict__ S, SeqTable seq, int total, int32_t* __restrict__ idx_out,
     float* __restrict__ sorted_out, uint2* __restrict__ pairs_a, uint2* __restrict__ pairs_b) {
-  typedef RankShared<SHORT ? 512 : RK_MAX_BINS, SHORT ? RK_SHORT_TILE : RK_TILE> Shared;
-  __shared__ Shared sh;
+  typedef RankShared<512, SHORT ? RK_SHORT_TILE : RK_THREADS * RK_ITEMS9> Shared9;
+  typedef RankShared<1024, SHORT ? RK_SHORT_TILE : RK_THREADS * RK_ITEMS10> Shared10;
+  constexpr size_t LDS_BYTES =
+      SHORT ? (sizeof(Shared9) > sizeof(RankSweepShared) ? sizeof(Shared9) : sizeof(RankSweepShared))
+            : (sizeof(Shared9) > sizeof(Shared10) ? sizeof(Shared9) : sizeof(Shared10));
+  static_assert(LDS_BYTES >= sizeof(RankSweepShared), "the sweep's counters fit too");
+  __shared__ __align__(16) unsigned char lds[LDS_BYTES];
   const int b = blockIdx.y;
   const int n = seq.cu[b + 1] - seq.cu[b];
   if (n == 0 || (SHORT && n > RK_SHORT_TILE)) return;
@@ -328,17 +411,14 @@ __global__ __launch_bounds__(RK_THREADS) void head_rank_kernel(
   const float* src_f = S + seg;
   const int tid = threadIdx.x;
 
-  // ---- counts of the lowest digit (as wide as the histogram allows: folded below if
-  // the passes use fewer bits) and of the top byte, in one sweep ----
+  // ---- counts of the lowest 10 key bits and of the top byte, in one sweep ----
   // Eight loads in flight per thread.  The top byte (sign and high exponent bits)
   // takes a handful of values in a whole segment, so its atomics would all hit a few
-  // addresses; it is counted in 32 bank-private copies instead, which live in the
-  // staging area (unused until the first pass) and are summed afterwards.
-  static_assert(Shared::tile * 2 >= 256 * 32, "staging area holds the 32 copies");
-  uint32_t* top_copies = reinterpret_cast<uint32_t*>(sh.stage);
-  if (tid < Shared::max_bins) sh.hist[0][tid] = 0;
-  for (int i = tid; i < 256 * 32; i += RK_THREADS) top_copies[i] = 0;
-  if (tid == 0) { sh.top_min = 255u; sh.top_max = 0u; }
+  // addresses; it is counted in 32 bank-private copies instead, summed afterwards.
+  RankSweepShared& sw = *reinterpret_cast<RankSweepShared*>(lds);
+  sw.low[tid] = 0;
+  for (int i = tid; i < 256 * 32; i += RK_THREADS) sw.top[i] = 0;
+  if (tid == 0) { sw.top_min = 255u; sw.top_max = 0u; }
   __syncthreads();
   {
     const float* sweep_f = uniform_ptr(src_f);
@@ -348,14 +428,14 @@ __global__ __launch_bounds__(RK_THREADS) void head_rank_kernel(
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         const int i = i0 + e * RK_THREADS + tid;
-        x[e] = at32(sweep_f, uint32_t(i < n ? i : n - 1));   // clamped: never past the segment
+        x[e] = load_item<STREAM>(&at32(sweep_f, uint32_t(i < n ? i : n - 1)));   // clamped: never past the segment
       }
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         if (i0 + e * RK_THREADS + tid < n) {
           const uint32_t key = desc_key(x[e]);
-          atomicAdd(&sh.hist[0][key & (Shared::max_bins - 1)], 1u);
-          atomicAdd(&top_copies[(key >> 24) * 32 + bank], 1u);
+          atomicAdd(&sw.low[key & (RK_MAX_BINS - 1)], 1u);
+          atomicAdd(&sw.top[(key >> 24) * 32 + bank], 1u);
         }
       }
     }
@@ -364,40 +444,49 @@ __global__ __launch_bounds__(RK_THREADS) void head_rank_kernel(
   if (tid < 256) {
     uint32_t sum = 0;
 #pragma unroll 8
-    for (int j = 0; j < 32; ++j) sum += top_copies[tid * 32 + ((j + tid) & 31)];
-    if (sum != 0) { atomicMin(&sh.top_min, (uint32_t)tid); atomicMax(&sh.top_max, (uint32_t)tid); }
+    for (int j = 0; j < 32; ++j) sum += sw.top[tid * 32 + ((j + tid) & 31)];
+    if (sum != 0) { atomicMin(&sw.top_min, (uint32_t)tid); atomicMax(&sw.top_max, (uint32_t)tid); }
   }
   __syncthreads();
   // keys minus (smallest top byte << 24) are below 2^(24 + span_bits)
-  const uint32_t top_min = sh.top_min, span = sh.top_max - top_min;
+  const uint32_t top_min = sw.top_min, span = sw.top_max - top_min;
   const uint32_t rebase = top_min << 24;
   const int span_bits = span == 0 ? 0 : 32 - __clz((int)span);
-  const bool ten = span_bits > 3 && span_bits <= 6;      // 28..30 bits: three passes of 10
-  const int passes = span_bits <= 6 ? 3 : 4;             // 9-bit digits otherwise: 27 or 36 bits
-  if (!SHORT && (!ten || n <= RK_TILE)) {                // (single tiles always take 9-bit digits)
-    // fold the 10-bit counts into 9-bit ones (every thread reads and writes its own entries)
-    if (tid < 512) sh.hist[0][tid] += sh.hist[0][tid + 512];
-  }
+  // 9-bit digits: three passes cover 27 bits, four cover everything; 10-bit digits:
+  // three passes cover 30 bits (long segments only: a single tile always takes 9)
+  const bool ten = !SHORT && n > RK_TILE && span_bits > 3 && span_bits <= 6;
+  const int passes = (span_bits <= 3 || ten) ? 3 : 4;
+  // the counts of the first digit move to where the layout of the passes wants them
+  uint32_t first = sw.low[tid];
+  if (!ten) first += sw.low[tid ^ 512];
   __syncthreads();
 
   float* out_f = sorted_out + seg;
   int32_t* out_i = idx_out + seg;
-  // one tile: the passes hand the data on through LDS; short segments take fewer
-  // items per lane (an unused item slot costs as much ranking work as a used one)
-  if (n <= RK_TILE) {
-    const int p1 = span_bits <= 3 ? 3 : 4;
+  if (!ten) {
+    Shared9& sh = *reinterpret_cast<Shared9*>(lds);
+    if (tid < 512) sh.hist[0][tid] = first;
+    __syncthreads();
+    // one tile: the passes hand the data on through LDS; short segments take fewer
+    // items per lane (an unused item slot costs as much ranking work as a used one)
     if (n <= RK_THREADS * 2) {
-      radix_sort<9, true, 2>(sh, n, p1, rebase, src_f, nullptr, nullptr, out_f, out_i);
+      radix_sort<9, true, 2, false>(sh, n, passes, rebase, src_f, nullptr, nullptr, out_f, out_i);
     } else if (SHORT || n <= RK_THREADS * 4) {
-      radix_sort<9, true, 4>(sh, n, p1, rebase, src_f, nullptr, nullptr, out_f, out_i);
+      radix_sort<9, true, 4, false>(sh, n, passes, rebase, src_f, nullptr, nullptr, out_f, out_i);
     } else if constexpr (!SHORT) {
-      radix_sort<9, true, RK_ITEMS>(sh, n, p1, rebase, src_f, nullptr, nullptr, out_f, out_i);
+      if (n <= RK_THREADS * 8) {
+        radix_sort<9, true, 8, false>(sh, n, passes, rebase, src_f, nullptr, nullptr, out_f, out_i);
+      } else if (n <= RK_TILE) {
+        radix_sort<9, true, RK_ITEMS9, false>(sh, n, passes, rebase, src_f, nullptr, nullptr, out_f, out_i);
+      } else {
+        radix_sort<9, false, RK_ITEMS9, STREAM>(sh, n, passes, rebase, src_f, pairs_a + seg, pairs_b + seg, out_f, out_i);
+      }
     }
-    return;
-  }
-  if constexpr (!SHORT) {
-    if (ten) radix_sort<10, false, RK_ITEMS>(sh, n, 3, rebase, src_f, pairs_a + seg, pairs_b + seg, out_f, out_i);
-    else radix_sort<9, false, RK_ITEMS>(sh, n, passes, rebase, src_f, pairs_a + seg, pairs_b + seg, out_f, out_i);
+  } else if constexpr (!SHORT) {
+    Shared10& sh = *reinterpret_cast<Shared10*>(lds);
+    sh.hist[0][tid] = first;
+    __syncthreads();
+    radix_sort<10, false, RK_ITEMS10, STREAM>(sh, n, 3, rebase, src_f, pairs_a + seg, pairs_b + seg, out_f, out_i);
   }
 }
 
@@ -457,11 +546,16 @@ kvc_status launch_head_rank(const Problem& pb, const float* S, int32_t* idx, flo
   uint2* pairs_a = static_cast<uint2*>(ws);
   uint2* pairs_b = reinterpret_cast<uint2*>(static_cast<char*>(ws) + align_up(lht * 8));
   dim3 grid(pb.layers * pb.hkv, pb.batch);
+  // one workgroup of the long-segment kernels per compute unit, 256 of them: what is in flight
+  const long resident = std::min<long>(long(grid.x) * grid.y, 256);
   if (pb.max_seqlen <= RK_SHORT_TILE) {
-    KVC_LAUNCH("head_rank_kernel", stream, head_rank_kernel<true><<<grid, RK_THREADS, 0, stream>>>(S, pb.seq, int(pb.total), idx, S_sorted,
+    KVC_LAUNCH("head_rank_kernel", stream, head_rank_kernel<true, false><<<grid, RK_THREADS, 0, stream>>>(S, pb.seq, int(pb.total), idx, S_sorted,
+                                                      pairs_a, pairs_b));
+  } else if (long(pb.max_seqlen) * resident >= RK_STREAM_ITEMS) {
+    KVC_LAUNCH("head_rank_kernel", stream, head_rank_kernel<false, true><<<grid, RK_THREADS, 0, stream>>>(S, pb.seq, int(pb.total), idx, S_sorted,
                                                       pairs_a, pairs_b));
   } else {
-    KVC_LAUNCH("head_rank_kernel", stream, head_rank_kernel<false><<<grid, RK_THREADS, 0, stream>>>(S, pb.seq, int(pb.total), idx, S_sorted,
+    KVC_LAUNCH("head_rank_kernel", stream, head_rank_kernel<false, false><<<grid, RK_THREADS, 0, stream>>>(S, pb.seq, int(pb.total), idx, S_sorted,
                                                       pairs_a, pairs_b));
   }
   return KVC_OK;
