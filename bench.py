@@ -113,7 +113,9 @@ def record_traffic(d: str, layers: int, commit: str) -> None:
     fetch, write = means("fetch", "FETCH_SIZE"), means("write", "WRITE_SIZE")
     label = {"score_mfma<false, true, 4>": "score_mfma<stats>",
              "score_mfma<true, true, 4>": "score_mfma<emit>",
-             "head_rank_kernel": "head_rank_kernel", "gather_kernel": "gather_kernel"}
+             "head_rank_kernel<false, false>": "head_rank_kernel",
+             "head_rank_kernel<false, true>": "head_rank_kernel",
+             "head_rank_kernel<true, false>": "head_rank_kernel", "gather_kernel": "gather_kernel"}
     kernels = {}
     for raw, (f, n) in fetch.items():
         key = next((v for k, v in label.items() if raw.replace(" ", "") == k.replace(" ", "")), raw)

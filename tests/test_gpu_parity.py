@@ -137,7 +137,7 @@ def _rank_inputs(kind, lyr, hkv, lens, seed):
 @pytest.mark.parametrize("kind", ["scores", "ties", "signed", "constant", "narrow", "span7", "span8",
                                   "span64"])
 @pytest.mark.parametrize("lens", [[1], [63], [2047], [2048, 2049], [4096], [4097], [8192, 8193],
-                                  [9000, 1, 300], [3000, 9000], [20000], [16384, 16385], [40000]])
+                                  [9000, 1, 300], [3000, 9000], [20000], [12288, 12289], [16384, 16385], [40000]])
 def test_head_rank_bit_exact(kind, lens):
     _say(f"rank {kind} lens={lens}")
     lyr, hkv = 2, 3
@@ -162,6 +162,27 @@ def test_head_rank_bit_exact(kind, lens):
         assert np.all(np.diff(gs[:, :, lo:hi], axis=-1) <= 0)
         np.testing.assert_array_equal(gs[:, :, lo:hi], np.take_along_axis(
             s[:, :, lo:hi], gi[:, :, lo:hi].astype(np.int64), axis=-1))
+
+
+@pytest.mark.parametrize("kind", ["scores", "narrow", "signed"])
+def test_head_rank_many_long_segments(kind):
+    """256 segments of 41000 scores: enough items in flight for the launch whose loads
+    carry the streaming hint; 10-bit, 9-bit and four-pass digit plans."""
+    _say(f"rank many long segments {kind}")
+    lyr, hkv, n = 16, 16, 41000
+    s = _rank_inputs(kind, lyr, hkv, [n], 3)
+    p = kv.KvcParams(1, lyr, hkv, hkv, 128, 64, kv.KVC_BF16)
+    ws_bytes = kv.kvc_workspace_size(p, n, n)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    S = to_dev(s)
+    idx = torch.full((lyr, hkv, n), -1, dtype=torch.int32, device="cuda")
+    ss = torch.zeros_like(S)
+    kv.kvc_head_rank(p, S.data_ptr(), [0, n], idx.data_ptr(), ss.data_ptr(), ws.data_ptr(), ws_bytes,
+                     stream())
+    torch.cuda.synchronize()
+    ri, rs = orc.head_rank(s.astype(np.float64))
+    np.testing.assert_array_equal(idx.cpu().numpy(), ri)
+    np.testing.assert_array_equal(ss.cpu().numpy(), rs.astype(np.float32))
 
 
 @pytest.mark.parametrize("agg_head", [kv.KVC_AGG_MEAN, kv.KVC_AGG_MAX])
