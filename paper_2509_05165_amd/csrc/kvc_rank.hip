@@ -19,9 +19,9 @@
 // store per item.  Within a tile every wave ranks its items with ballot-based
 // digit matching and lane prefix counts; per-wave digit counters live in LDS.
 //
-// A segment that fits one tile (n <= 8192) never leaves the chip between the
+// A segment that fits one tile (n <= 12288) never leaves the chip between the
 // passes: the digit-ordered staging area of one pass is the input of the next,
-// global memory sees one read of the scores and one write of the result.
+// global memory sees the sweep, one read of the scores and one write of the result.
 #include "kvc_internal.h"
 
 namespace kvc {
@@ -223,7 +223,7 @@ __device__ __forceinline__ void rank_and_stage(SH& sh, const uint32_t (&key)[ITE
     }
     const uint32_t incl = wave_inclusive_sum(mine);
     local_start = incl - mine;                 // exclusive within the wave
-    if (lane == 63) sh.wave_tot[wave] = incl;  // (free since the bucket scan of the pass start)
+    if (lane == 63) sh.wave_tot[wave] = incl;  // (not in use since the bucket scan at the start of the pass)
   }
   lds_barrier();
   if (tid < BINS) {
@@ -348,7 +348,7 @@ __device__ __forceinline__ void radix_pass(SH& sh, int n, int shift, int hsel,
     }                                                                              \
   }
     if (!LOUT) {
-      // (the thread's slot base is made opaque here, so that the sixteen slot addresses
+      // (the thread's slot base is made opaque here, so that the slot addresses
       // are formed where they are used instead of being kept, and spilled, across the
       // tile loop; four items at a time keep the temporaries of the write-out few)
       int stid = tid;
