@@ -13,6 +13,8 @@ Other modes (each prints one JSON line and exits):
   --sustain KIND[,KIND..] --seconds S   loop one stage (or a probe) for S seconds
         while a host thread samples shader clock and socket power; KIND is one
         of compress, score, rank, gather, mfma, mfma_stats, copy
+  --graph                               the timed steps replay one kvc_compress call
+        recorded in a HIP graph (for the small, launch-heavy workloads)
   --copy-probe MB                       the plain copy kernel (counter calibration)
   --record-traffic DIR                  turn rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
         csv output under DIR into profiles/hbm_traffic.json (no GPU needed)
@@ -308,6 +310,8 @@ def main():
     ap.add_argument("--n", type=int, default=None, help="override context length (debug)")
     ap.add_argument("--layers", type=int, default=None, help="override layer count (debug)")
     ap.add_argument("--batch", type=int, default=None, help="override number of sequences (debug)")
+    ap.add_argument("--graph", action="store_true",
+                    help="time replays of one kvc_compress call recorded in a HIP graph (small workloads)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probe", action="store_true", help="skip the MFMA ceiling probe")
     ap.add_argument("--cpu-layers", type=int, default=8)
@@ -385,12 +389,21 @@ def main():
                 lengths, offsets, k_out, v_out)
         return
 
+    timed_step = step
+    if args.graph:
+        # the library only enqueues kernels, so a call can be recorded once and replayed
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            cs = torch.cuda.current_stream().cuda_stream
+            kv.kvc_compress(p, qp, kp, vp, cu, budgets, k_out.data_ptr(), v_out.data_ptr(),
+                            lengths.data_ptr(), offsets.data_ptr(), ws.data_ptr(), ws_bytes, cs)
+        timed_step = graph.replay
     for _ in range(args.warmup):
-        step()
+        timed_step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step()
+        timed_step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed * 1e3 / args.steps
@@ -503,7 +516,8 @@ def main():
                                f"{cfg.layers} layers, {cfg.hq}/{cfg.hkv} heads, d={cfg.head_dim}, "
                                f"N={max_n}, M={cfg.window}, keep {cfg.keep_percent}%"
                                + (", causal tail" if cfg.causal_tail else ""),
-                   "total_tokens": total, "budget": tb, "seed": args.seed},
+                   "total_tokens": total, "budget": tb, "seed": args.seed,
+                   "launch": "hip graph replay" if args.graph else "eager"},
         "roofline": roofline, "stages_ms": stages, "stage_rates": hbm,
     }
     if not args.no_cpu_baseline:
