@@ -144,9 +144,9 @@ __device__ __forceinline__ int lanes_below(uint64_t mask) {
 // LDS of one workgroup during the passes, for digits of MAXBINS values and tiles
 // of up to TILE items.  The tile is as large as LDS allows, because the length of
 // a digit run in the write-out (TILE / MAXBINS items of 8 bytes) is what the
-// memory system's write rate follows: (512, 16384) and (1024, 12288) take 154 and
-// 148 KB, one workgroup per compute unit; the launch for batches of short
-// sequences uses (512, 4096), 58 KB, so that two workgroups share a compute unit
+// memory system's write rate follows: (512, 12288) and (1024, 12288) take 120 and
+// 144 KB, one workgroup per compute unit; the launch for batches of short
+// sequences uses (512, 4096), 56 KB, so that two workgroups share a compute unit
 // and hide each other's barriers and load latencies.  Per-wave digit counts never
 // exceed the tile size and are kept in 16 bits.
 template <int MAXBINS, int TILE>
@@ -159,7 +159,6 @@ struct RankShared {
   uint32_t hist[2][MAXBINS];           // digit counts of the running pass and of the next one
   uint32_t bucket[MAXBINS];            // next free global slot of each digit
   uint16_t wave_cnt[RK_WAVES][MAXBINS];
-  uint32_t tstart[MAXBINS];            // first tile-local slot of each digit
   uint32_t gbase[MAXBINS];             // global slot of an item = gbase[digit] + tile-local slot
   uint32_t wave_tot[RK_WAVES];
 };
@@ -209,18 +208,15 @@ __device__ __forceinline__ void rank_and_stage(SH& sh, const uint32_t (&key)[ITE
     __builtin_amdgcn_wave_barrier();
   }
   lds_barrier();
-  // one thread per digit: per-wave counts -> prefixes inside the digit, digit
-  // totals -> tile-local start slots and the global base (conflict-free columns)
+  // one thread per digit: digit totals -> tile-local start slots and the global base,
+  // per-wave counts -> first slot of each wave's items of the digit (conflict-free columns)
   uint32_t mine = 0, local_start = 0;
   int dtid = tid;                              // (opaque: the addresses of this step are not
   asm volatile("" : "+v"(dtid));               // worth registers across the ranking loop)
+  uint32_t cnt[RK_WAVES];
   if (tid < BINS) {
 #pragma unroll
-    for (int w = 0; w < RK_WAVES; ++w) {
-      const uint32_t c = sh.wave_cnt[w][dtid];
-      sh.wave_cnt[w][dtid] = uint16_t(mine);   // items of this digit in the waves before w
-      mine += c;
-    }
+    for (int w = 0; w < RK_WAVES; ++w) { cnt[w] = sh.wave_cnt[w][dtid]; mine += cnt[w]; }
     const uint32_t incl = wave_inclusive_sum(mine);
     local_start = incl - mine;                 // exclusive within the wave
     if (lane == 63) sh.wave_tot[wave] = incl;  // (not in use since the bucket scan at the start of the pass)
@@ -230,9 +226,13 @@ __device__ __forceinline__ void rank_and_stage(SH& sh, const uint32_t (&key)[ITE
     uint32_t start = local_start;
     for (int w = 0; w < wave; ++w) start += sh.wave_tot[w];
     const uint32_t g = sh.bucket[dtid];
-    sh.tstart[dtid] = start;
     sh.gbase[dtid] = g - start;
     sh.bucket[dtid] = g + mine;
+    // the counters now become the first tile-local slot of each wave's share of the
+    // digit, so that placing an item costs one LDS read
+    uint32_t run = start;
+#pragma unroll
+    for (int w = 0; w < RK_WAVES; ++w) { sh.wave_cnt[w][dtid] = uint16_t(run); run += cnt[w]; }
   }
   lds_barrier();
   // every item goes to its tile-local slot
@@ -240,7 +240,7 @@ __device__ __forceinline__ void rank_and_stage(SH& sh, const uint32_t (&key)[ITE
   for (int e = 0; e < ITEMS; ++e) {
     if (wbase + e * 64 < n) {
       const uint32_t digit = (key[e] >> shift) & DMASK;
-      const uint32_t slot = sh.tstart[digit] + sh.wave_cnt[wave][digit] + ((rank2[e / 2] >> (16 * (e & 1))) & 0xffffu);
+      const uint32_t slot = sh.wave_cnt[wave][digit] + ((rank2[e / 2] >> (16 * (e & 1))) & 0xffffu);
       sh.stage[slot] = make_uint2(key[e], KIND == RK_FIRST ? uint32_t(wbase + e * 64) : uint32_t(val[e]));
     }
     if (e % 4 == 3) __builtin_amdgcn_sched_barrier(0);   // (four items' temporaries at a time)
